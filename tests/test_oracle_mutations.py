@@ -1,0 +1,65 @@
+"""The pins must notice plausible mistakes in the oracle.
+
+Each case below plants ONE mistake in a private copy of `oracle/e4q_oracle.c` (on the CPU, in a
+temporary directory), rebuilds it and re-runs `test_oracle_pins.py` against that copy: the run
+must fail.  The test that compares the C oracle with its NumPy twin is left out of those runs,
+because agreement between two implementations of one reading is not a pin.
+"""
+import os
+import shutil
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+MUTANTS = {
+    "sixteen_levels": ("#define E4Q_QMAX 15.0f", "#define E4Q_QMAX 16.0f"),
+    "tie_moves_lower_bound": ("if (loss_l < loss_r) {", "if (loss_l <= loss_r) {"),
+    "later_equal_loss_wins": ("if (loss_r < best.loss) {", "if (loss_r <= best.loss) {"),
+    "upper_bound_moves_up": ("float next_max = cur_max - stepsize;", "float next_max = cur_max + stepsize;"),
+    "round_half_up": ("float q = rintf(t);", "float q = floorf(t + 0.5f);"),
+    "truncate": ("float q = rintf(t);", "float q = truncf(t);"),
+    "strided_sum_tree": ("s[i] = s[2 * i] + s[2 * i + 1];", "s[i] = s[i] + s[i + m / 2];"),
+    "nibbles_swapped": ("codes[b] = (uint8_t)(q0 | (q1 << 4));", "codes[b] = (uint8_t)(q1 | (q0 << 4));"),
+    "search_ignores_fp16_storage": ("*scale = round_through_f16(scale32);", "*scale = scale32;"),
+    "no_upper_clamp": ("if (q > E4Q_QMAX) q = E4Q_QMAX;", ""),
+    "no_lower_clamp": ("if (q < 0.0f) q = 0.0f;", "if (q < 0.0f) q = -q;"),
+    "step_off_by_one": ("float stepsize = (hi0 - lo0) / (float)n_bins;\n    float cur_min",
+                        "float stepsize = (hi0 - lo0) / (float)(n_bins - 1);\n    float cur_min"),
+    "floor_trip_count": ("double t = ceil(br - br * 0x1p-22);", "double t = floor(br);"),
+    "start_not_a_candidate": ("best.loss = range_loss(x, d, lo0, hi0, work);", "best.loss = INFINITY;"),
+    "literal_bookkeeping_by_default": ("if (!literal_alg1) { best.xmax = cur_max; best.j = j; }",
+                                       "if (literal_alg1) { best.xmax = cur_max; best.j = j; }"),
+    "dequantize_nibbles_swapped": ("unsigned q = (k & 1) ? (byte >> 4) : (byte & 0xfu);\n            out[r * dim + k] = fmaf",
+                                   "unsigned q = (k & 1) ? (byte & 0xfu) : (byte >> 4);\n            out[r * dim + k] = fmaf"),
+    "bias_is_not_xmin": ("*bias_f16 = e4q_oracle_f32_to_f16(lo);", "*bias_f16 = e4q_oracle_f32_to_f16(hi);"),
+    "error_not_squared": ("work[k] = e * e;", "work[k] = fabsf(e);"),
+    "f16_ties_away": ("if (rem > 0x1000u || (rem == 0x1000u && (h & 1u)))", "if (rem >= 0x1000u)"),
+}
+
+
+def _run_pins(oracle_parent):
+    env = dict(os.environ)
+    if oracle_parent:
+        env["E4Q_TEST_ORACLE_PARENT"] = oracle_parent
+    return subprocess.run(
+        [sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", "test_oracle_pins.py"), "-x", "-q",
+         "-k", "not numpy_twin", "-p", "no:cacheprovider"],
+        cwd=ROOT, env=env, capture_output=True, text=True, timeout=600)
+
+
+@pytest.mark.parametrize("name", sorted(MUTANTS))
+def test_pins_catch_planted_mistake(name, tmp_path):
+    old, new = MUTANTS[name]
+    dst = tmp_path / "oracle"
+    dst.mkdir()
+    for f in ("__init__.py", "numpy_twin.py", "e4q_oracle.c"):
+        shutil.copy(os.path.join(ROOT, "oracle", f), dst / f)
+    src = (dst / "e4q_oracle.c").read_text()
+    assert src.count(old) >= 1, f"mutation site for {name} no longer exists in the oracle"
+    (dst / "e4q_oracle.c").write_text(src.replace(old, new))
+    res = _run_pins(str(tmp_path))
+    assert res.returncode != 0, f"pins did not notice mutant '{name}':\n{res.stdout[-2000:]}"
+    assert "failed" in res.stdout or "error" in res.stdout.lower()

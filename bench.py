@@ -1,0 +1,194 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X: row-wise greedy 4-bit quantization of a seeded
+synthetic embedding table (then de-quantization of the result), through libe4q's C ABI.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload laplace_10M_x_128]
+
+One "step" is one pass of the whole path over the table, which is already resident in HBM:
+`quantize_rowwise_greedy` (row load, min/max, Algorithm 1's search, encode + pack, binary16
+scale/bias) followed by `dequantize` of its output.  Prints ONE JSON line.  `value` is rows per
+second over whole steps; the `kernels` object gives each kernel's own average duration from HIP
+events recorded on the launch stream inside the timed region; `roofline` prices the dominant
+kernel (the greedy search, bound by plain fp32 VALU issue); `cpu_baseline` is the CPU oracle
+timed on this machine's host cores on a bounded sample of the same table.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import re
+import sys
+import time
+from concurrent.futures import ThreadPoolExecutor
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# MI355X: 256 CUs x 4 SIMDs x 16 fp32 lanes at 2.4 GHz, one plain (non-packed) VALU operation per
+# lane per clock.  The data-sheet 157.3 TFLOP/s is this figure x 2 (packed fp32) x 2 (FMA = 2 flops);
+# packed fp32 is switched off in this build and 7 of the 8 operations per element are not FMAs.
+PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
+PEAK_HBM_BYTES = 8.0e12
+
+WORKLOADS = {
+    # name: (generator, rows, dim, n_bins, ratio)
+    "gaussian_10k_x_64": ("gaussian_table", 10_000, 64, 200, 0.16),
+    "outlier_1M_x_64": ("outlier_table", 1_000_000, 64, 200, 0.16),
+    "laplace_10M_x_128": ("laplace_offset_table", 10_000_000, 128, 200, 0.16),
+}
+
+
+def algorithmic_lane_ops_per_row(dim: int, n_iter: int) -> int:
+    """fp32 lane operations the method itself needs per row: 8 per element per scored range
+    (subtract, multiply, round, clamp, fused multiply-add, subtract, multiply, add) for the
+    1 + 2*n_iter ranges of Algorithm 1, 2 per element for min/max, 6 per element for the final
+    encode and pack."""
+    return (1 + 2 * n_iter) * dim * 8 + 2 * dim + 6 * dim
+
+
+def algorithmic_bytes_per_row(dim: int, elem_bytes: int = 4) -> int:
+    """Row read once, packed codes + binary16 scale and bias written once."""
+    return dim * elem_bytes + (dim + 1) // 2 + 4
+
+
+def read_traffic(name: str):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE runs); the
+    summary under profiles/ carries a line `traffic_bytes_per_launch: <int>`."""
+    path = os.path.join(ROOT, "profiles", name)
+    try:
+        m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), flags=re.M)
+        return float(m.group(1)) if m else None
+    except OSError:
+        return None
+
+
+def cpu_baseline(table_gpu, n_bins: int, ratio: float, target_seconds: float = 15.0):
+    """Times the CPU oracle (as it stands) on a prefix of the same table, rows partitioned over
+    the host cores available to this process (16 at most)."""
+    import numpy as np
+
+    import oracle
+
+    cores = max(1, min(16, len(os.sched_getaffinity(0))))
+    rows = table_gpu.shape[0]
+    probe = np.ascontiguousarray(table_gpu[: min(rows, 2048)].cpu().numpy())
+    t0 = time.perf_counter()
+    oracle.quantize_rowwise_greedy(probe, n_bins, ratio)
+    per_row = (time.perf_counter() - t0) / probe.shape[0]
+    sample_rows = int(min(rows, max(cores * 64, target_seconds * cores / per_row)))
+    sample = np.ascontiguousarray(table_gpu[:sample_rows].cpu().numpy())
+    bounds = [sample_rows * k // cores for k in range(cores + 1)]
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(max_workers=cores) as pool:  # ctypes releases the GIL inside the C call
+        list(pool.map(lambda k: oracle.quantize_rowwise_greedy(sample[bounds[k]:bounds[k + 1]], n_bins, ratio),
+                      range(cores)))
+    dt = time.perf_counter() - t0
+    return {"value": sample_rows / dt, "unit": "rows/s", "cores": cores, "kind": "oracle",
+            "sample": f"first {sample_rows} rows of the same table, rows split over {cores} threads, "
+                      f"{dt:.1f} s wall; single-thread probe {1e6 * per_row:.1f} us/row"}
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="laplace_10M_x_128", choices=sorted(WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only: this build has no multi-GPU path (rows shard with no "
+              "communication; run one process per GPU on its own row range).", file=sys.stderr)
+        return 2
+
+    import torch
+
+    import paper_1911_02079_amd as e4q
+    from paper_1911_02079_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    e4q.binding.load_library()
+    torch.cuda.set_device(0)
+    gen, rows, dim, n_bins, ratio = WORKLOADS[args.workload]
+    n_iter = e4q.greedy_iterations(n_bins, ratio)
+
+    table = getattr(synth, gen)(rows, dim, device="cuda:0")
+    out = e4q.alloc_outputs(rows, dim, table.device)
+    xh = torch.empty((rows, dim), dtype=torch.float32, device=table.device)
+    torch.cuda.synchronize()
+
+    def step(events=None):
+        if events is not None:
+            events[0].record()
+        e4q.quantize_rowwise_greedy(table, n_bins, ratio, out=out)
+        if events is not None:
+            events[1].record()
+        e4q.dequantize(out[0], out[1], out[2], dim, out=xh)
+        if events is not None:
+            events[2].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    # events live on torch's current stream, which is the stream handed to the library
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(evs[k])
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    ms_per_step = 1e3 * elapsed / args.steps
+    greedy_ms = sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps
+    dequant_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps
+
+    lane_ops = algorithmic_lane_ops_per_row(dim, n_iter) * rows
+    q_bytes = algorithmic_bytes_per_row(dim) * rows
+    dq_bytes = ((dim + 1) // 2 + 4 + 4 * dim) * rows
+    achieved = lane_ops / (greedy_ms * 1e-3)
+    result = {
+        "metric": "rows quantized/sec (greedy 4-bit)",
+        "value": rows / (elapsed / args.steps),
+        "unit": "rows/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "rows": rows, "dim": dim, "n_bins": n_bins, "ratio": ratio,
+                   "candidate_ranges_per_row": 1 + 2 * n_iter, "nbits": 4,
+                   "step": "quantize_rowwise_greedy + dequantize, table resident in HBM"},
+        "kernels": {
+            "greedy_rpl_kernel": {"avg_ms": greedy_ms, "rows_per_s": rows / (greedy_ms * 1e-3),
+                                  "algorithmic_GBps": q_bytes / (greedy_ms * 1e-3) / 1e9},
+            "dequantize_w8_kernel": {"avg_ms": dequant_ms, "algorithmic_GBps": dq_bytes / (dequant_ms * 1e-3) / 1e9,
+                                     "frac_of_hbm_peak": dq_bytes / (dequant_ms * 1e-3) / PEAK_HBM_BYTES},
+        },
+        "roofline": {
+            "kernel": "greedy_rpl_kernel", "bound": "alu", "achieved": achieved / 1e12,
+            "peak": PEAK_LANE_OPS / 1e12, "unit": "T lane-op/s (plain fp32 VALU: 256 CU x 64 lanes x 2.4 GHz)",
+            "frac": achieved / PEAK_LANE_OPS,
+            "lane_ops_per_row": algorithmic_lane_ops_per_row(dim, n_iter),
+            "bytes_per_row": algorithmic_bytes_per_row(dim),
+            "hbm_achieved_GBps": q_bytes / (greedy_ms * 1e-3) / 1e9,
+            "hbm_frac": q_bytes / (greedy_ms * 1e-3) / PEAK_HBM_BYTES,
+            "traffic": read_traffic(f"greedy_rpl_kernel_{args.workload}_hbm_traffic.txt"),
+        },
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(table, n_bins, ratio)
+    print(json.dumps(result), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,139 @@
+/*
+ * e4q.h -- C ABI of libe4q: row-wise 4-bit quantization of embedding tables on one
+ * AMD MI355X (gfx950), after "Post-Training 4-bit Quantization on Embedding Tables"
+ * (arXiv 1911.02079).
+ *
+ * Conventions that hold for every call
+ * ------------------------------------
+ *  - Every data pointer is a DEVICE pointer into memory the caller owns (for example a
+ *    PyTorch tensor's storage).  The library never frees or reallocates caller memory, keeps
+ *    no pointer after the call returns, and allocates nothing that outlives a call.
+ *  - `hip_stream` is a hipStream_t passed as an opaque pointer (NULL = the null stream).
+ *    Calls are asynchronous: kernels are enqueued on that stream and the call returns; the
+ *    library never synchronises the device.  Inputs must stay valid and outputs must not be
+ *    read until the stream has reached the end of the enqueued work.
+ *  - The current HIP device must be the one that owns the buffers.
+ *  - Return value: E4Q_OK (0) on success, a negative E4Q_ERR_* code otherwise; no exception
+ *    or signal crosses the boundary.  Arguments are validated before anything is launched, so
+ *    a failed call has written nothing.  rows == 0 is a successful no-op.
+ *  - Tables are row-major.  `row_stride` is the distance between consecutive rows in ELEMENTS
+ *    (>= dim).  Packed codes are dense: ceil(dim/2) bytes per row, no padding between rows;
+ *    element 2k sits in the low nibble and element 2k+1 in the high nibble of byte k; for odd
+ *    dim the last high nibble is 0.  scale, bias and codebook entries are IEEE binary16 bit
+ *    patterns stored as uint16_t.
+ *  - Inputs containing NaN or infinities, and rows whose minimum or range exceeds the
+ *    binary16 range (65504), give unspecified codes and parameters (never a fault).
+ */
+#ifndef E4Q_H
+#define E4Q_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Error codes. */
+#define E4Q_OK 0
+#define E4Q_ERR_NULL_POINTER (-1)   /* a required pointer is NULL */
+#define E4Q_ERR_BAD_SHAPE (-2)      /* rows < 0, dim <= 0, dim > E4Q_MAX_DIM, row_stride < dim */
+#define E4Q_ERR_BAD_NBITS (-3)      /* nbits != 4 */
+#define E4Q_ERR_BAD_SEARCH (-4)     /* n_bins < 1, ratio outside [0, 1), ratio NaN, lloyd_iters < 0 */
+#define E4Q_ERR_BAD_DTYPE (-5)      /* dtype is neither E4Q_F32 nor E4Q_F16 */
+#define E4Q_ERR_LAUNCH (-6)         /* HIP reported an error when the kernel was enqueued */
+#define E4Q_ERR_BAD_ALIGNMENT (-7)  /* table pointer not aligned to its element size */
+
+/* Element type of an input table. */
+#define E4Q_F32 0
+#define E4Q_F16 1
+
+/* Largest supported embedding dimension. */
+#define E4Q_MAX_DIM 4096
+
+/*
+ * Row-wise uniform 4-bit quantization with greedy search of the clipping range
+ * (Algorithm 1; quantizer and stored parameters of Eq. 1; loss of Eq. 2; binary16 scale and
+ * bias as in the "(FP16)" variants of Section 4).
+ *
+ * For each row X independently: start from [min X, max X], stepsize = (max - min)/n_bins;
+ * n_iter = ceil(n_bins * ratio) times (at most n_bins - 1) score "lower bound up one step"
+ * against "upper bound down one step" by the squared quantize->dequantize error of the row,
+ * move the bound with the smaller error (ties move the upper bound) and remember the range
+ * with the smallest error seen (strictly smaller replaces; the pair of bounds is remembered
+ * together).  The row is then encoded with that range: scale = (xmax - xmin)/15 and
+ * bias = xmin rounded to binary16, code = clamp(round_half_even((x - bias) * (1/scale)), 0, 15),
+ * all in binary32.  Candidates are scored with the binary16-rounded parameters, i.e. with
+ * what is stored.  ratio == 0 gives plain min/max ("ASYM") quantization.  A row with
+ * max == min, or whose scale rounds to 0 in binary16, gets scale 0 and all codes 0.
+ *
+ *   table       [in]  rows x dim elements of `dtype`, `row_stride` elements between rows
+ *   dtype             E4Q_F32 or E4Q_F16 (binary16 inputs are widened exactly)
+ *   nbits             must be 4
+ *   n_bins            b of Algorithm 1 (default in the paper: 200)
+ *   ratio             r of Algorithm 1 (default in the paper: 0.16), 0 <= ratio < 1
+ *   codes       [out] rows x ceil(dim/2) bytes
+ *   scale_f16   [out] rows binary16 values
+ *   bias_f16    [out] rows binary16 values
+ */
+int e4q_quantize_rowwise_greedy(const void* table, int dtype, int64_t rows, int32_t dim,
+                                int64_t row_stride, int32_t nbits, int32_t n_bins, float ratio,
+                                uint8_t* codes, uint16_t* scale_f16, uint16_t* bias_f16,
+                                void* hip_stream);
+
+/*
+ * De-quantization x_float = scale * x_int + bias (the sentence after Eq. 1), one fused
+ * multiply-add per element in binary32.
+ *
+ *   codes, scale_f16, bias_f16  [in]  as written by e4q_quantize_rowwise_greedy
+ *   out                         [out] rows x dim binary32, dense (row stride = dim)
+ */
+int e4q_dequantize(const uint8_t* codes, const uint16_t* scale_f16, const uint16_t* bias_f16,
+                   int64_t rows, int32_t dim, int32_t nbits, float* out, void* hip_stream);
+
+/*
+ * One table of a batch.  The array of descriptors itself lives in HOST memory and is only
+ * read during the call; the pointers inside are device pointers with the meaning they have in
+ * e4q_quantize_rowwise_greedy.
+ */
+typedef struct e4q_table_desc {
+    const void* table;
+    int32_t dtype;
+    int32_t dim;
+    int64_t rows;
+    int64_t row_stride;
+    uint8_t* codes;
+    uint16_t* scale_f16;
+    uint16_t* bias_f16;
+} e4q_table_desc;
+
+/*
+ * Greedy quantization (as above) of `n_tables` tables in one launch sequence on one stream:
+ * all descriptors are validated first, then every table's work is enqueued back to back with
+ * no host synchronisation in between.  On a validation error nothing is enqueued.
+ */
+int e4q_quantize_rowwise_greedy_batch(const e4q_table_desc* descs, int32_t n_tables,
+                                      int32_t nbits, int32_t n_bins, float ratio,
+                                      void* hip_stream);
+
+/*
+ * n_iter = ceil(n_bins * ratio) clamped to [0, n_bins - 1]: the number of trips of the loop of
+ * Algorithm 1 in exact arithmetic (each trip scores two candidate ranges).  `ratio` is a
+ * binary32 number and may sit a relative 2^-24 off the decimal the caller wrote, so the product
+ * is shrunk by a relative 2^-22 before the ceiling.  Host-only helper; returns a negative
+ * error code for invalid arguments.
+ */
+int32_t e4q_greedy_iterations(int32_t n_bins, float ratio);
+
+/* Static, human-readable text for a return code (never NULL). */
+const char* e4q_strerror(int code);
+
+/* Text of the last HIP error seen by this thread inside the library ("" if none). */
+const char* e4q_last_hip_error(void);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int e4q_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* E4Q_H */

@@ -1,0 +1,24 @@
+"""Row-wise greedy 4-bit quantization of embedding tables on MI355X (arXiv 1911.02079).
+
+The product is `libe4q.so` (hand-written HIP kernels behind the C ABI of `include/e4q.h`);
+this package holds its sources (`csrc/`), the build step (`build.py`), a ctypes binding with the
+same entry-point names (`binding.py`, imported lazily so that the package itself imports without
+the built library) and seeded synthetic-table generators (`synth.py`).
+"""
+from . import synth  # noqa: F401
+
+__all__ = ["synth", "binding", "quantize_rowwise_greedy", "quantize_rowwise_greedy_batch", "dequantize",
+           "greedy_iterations"]
+
+
+def __getattr__(name):
+    if name == "binding":
+        import importlib
+
+        return importlib.import_module(".binding", __name__)
+    if name in ("quantize_rowwise_greedy", "quantize_rowwise_greedy_batch", "dequantize", "greedy_iterations",
+                "alloc_outputs", "load_library", "E4QError"):
+        import importlib
+
+        return getattr(importlib.import_module(".binding", __name__), name)
+    raise AttributeError(name)

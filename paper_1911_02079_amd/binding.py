@@ -1,0 +1,183 @@
+"""ctypes binding of libe4q.so -- argument marshalling only.
+
+Every function here has the name of the C entry point it calls (minus the `e4q_` prefix) and
+does nothing but check tensor types, allocate outputs with torch and pass device pointers, sizes
+and the current HIP stream across the C ABI declared in `include/e4q.h`.  All arithmetic runs in
+the HIP kernels.  There is no CPU fallback: without the built library, or with tensors that are
+not on a GPU, these functions raise.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libe4q.so")
+
+E4Q_F32, E4Q_F16 = 0, 1
+_lib = None
+
+
+class E4QError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"libe4q error {code}: {text}")
+        self.code = code
+
+
+class TableDesc(ctypes.Structure):
+    """Mirror of `e4q_table_desc`."""
+    _fields_ = [("table", ctypes.c_void_p), ("dtype", ctypes.c_int32), ("dim", ctypes.c_int32),
+                ("rows", ctypes.c_int64), ("row_stride", ctypes.c_int64), ("codes", ctypes.c_void_p),
+                ("scale_f16", ctypes.c_void_p), ("bias_f16", ctypes.c_void_p)]
+
+
+def load_library() -> ctypes.CDLL:
+    """Load libe4q.so; raises if it has not been built (python -m paper_1911_02079_amd.build)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_1911_02079_amd.build` "
+                          "(there is no fallback implementation)")
+    lib = ctypes.CDLL(LIB_PATH)
+    c = ctypes
+    lib.e4q_quantize_rowwise_greedy.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int32, c.c_int64,
+                                                c.c_int32, c.c_int32, c.c_float, c.c_void_p, c.c_void_p,
+                                                c.c_void_p, c.c_void_p]
+    lib.e4q_quantize_rowwise_greedy.restype = c.c_int
+    lib.e4q_quantize_rowwise_greedy_batch.argtypes = [c.POINTER(TableDesc), c.c_int32, c.c_int32, c.c_int32,
+                                                      c.c_float, c.c_void_p]
+    lib.e4q_quantize_rowwise_greedy_batch.restype = c.c_int
+    lib.e4q_dequantize.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_int64, c.c_int32, c.c_int32,
+                                   c.c_void_p, c.c_void_p]
+    lib.e4q_dequantize.restype = c.c_int
+    lib.e4q_greedy_iterations.argtypes = [c.c_int32, c.c_float]
+    lib.e4q_greedy_iterations.restype = c.c_int32
+    lib.e4q_strerror.argtypes = [c.c_int]
+    lib.e4q_strerror.restype = c.c_char_p
+    lib.e4q_last_hip_error.argtypes = []
+    lib.e4q_last_hip_error.restype = c.c_char_p
+    lib.e4q_version.argtypes = []
+    lib.e4q_version.restype = c.c_int
+    _lib = lib
+    return lib
+
+
+def _check(code: int) -> None:
+    if code != 0:
+        lib = load_library()
+        text = lib.e4q_strerror(code).decode()
+        hip = lib.e4q_last_hip_error().decode()
+        raise E4QError(code, text + (f" [{hip}]" if hip and code == -6 else ""))
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return E4Q_F32
+    if t.dtype == torch.float16:
+        return E4Q_F16
+    raise TypeError(f"table must be float32 or float16, got {t.dtype}")
+
+
+def _check_table(t: torch.Tensor) -> None:
+    if not t.is_cuda:
+        raise ValueError("libe4q works on device memory only: the table must be a GPU tensor")
+    if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
+        raise ValueError("table must be 2-D with contiguous rows")
+
+
+def _stream_ptr(stream: Optional[torch.cuda.Stream], device) -> int:
+    s = stream if stream is not None else torch.cuda.current_stream(device)
+    return int(s.cuda_stream)
+
+
+def version() -> int:
+    return int(load_library().e4q_version())
+
+
+def strerror(code: int) -> str:
+    return load_library().e4q_strerror(int(code)).decode()
+
+
+def greedy_iterations(n_bins: int, ratio: float) -> int:
+    n = int(load_library().e4q_greedy_iterations(int(n_bins), float(ratio)))
+    if n < 0:
+        _check(n)
+    return n
+
+
+def alloc_outputs(rows: int, dim: int, device) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
+    """Output buffers of the layout the library writes: codes uint8 [rows, ceil(dim/2)],
+    scale and bias float16 [rows]."""
+    codes = torch.empty((rows, (dim + 1) // 2), dtype=torch.uint8, device=device)
+    scale = torch.empty((rows,), dtype=torch.float16, device=device)
+    bias = torch.empty((rows,), dtype=torch.float16, device=device)
+    return codes, scale, bias
+
+
+def quantize_rowwise_greedy(table: torch.Tensor, n_bins: int = 200, ratio: float = 0.16, nbits: int = 4,
+                            out: Optional[Tuple[torch.Tensor, torch.Tensor, torch.Tensor]] = None,
+                            stream: Optional[torch.cuda.Stream] = None):
+    """e4q_quantize_rowwise_greedy on a GPU tensor.  Returns (codes, scale_f16, bias_f16);
+    asynchronous on the given (default: current) stream."""
+    lib = load_library()
+    _check_table(table)
+    rows, dim = table.shape
+    codes, scale, bias = out if out is not None else alloc_outputs(rows, dim, table.device)
+    with torch.cuda.device(table.device):
+        rc = lib.e4q_quantize_rowwise_greedy(table.data_ptr(), _dtype_code(table), rows, dim,
+                                             table.stride(0) if rows > 1 else max(dim, table.stride(0)),
+                                             int(nbits), int(n_bins), float(ratio), codes.data_ptr(),
+                                             scale.data_ptr(), bias.data_ptr(), _stream_ptr(stream, table.device))
+    _check(rc)
+    return codes, scale, bias
+
+
+def quantize_rowwise_greedy_batch(tables: Sequence[torch.Tensor], n_bins: int = 200, ratio: float = 0.16,
+                                  nbits: int = 4, out: Optional[List[Tuple[torch.Tensor, ...]]] = None,
+                                  stream: Optional[torch.cuda.Stream] = None):
+    """e4q_quantize_rowwise_greedy_batch: all tables in one launch sequence on one stream."""
+    lib = load_library()
+    if len(tables) == 0:
+        return []
+    for t in tables:
+        _check_table(t)
+    device = tables[0].device
+    outs = out if out is not None else [alloc_outputs(t.shape[0], t.shape[1], device) for t in tables]
+    descs = (TableDesc * len(tables))()
+    for d, t, (codes, scale, bias) in zip(descs, tables, outs):
+        d.table, d.dtype, d.dim, d.rows = t.data_ptr(), _dtype_code(t), t.shape[1], t.shape[0]
+        d.row_stride = t.stride(0) if t.shape[0] > 1 else max(t.shape[1], t.stride(0))
+        d.codes, d.scale_f16, d.bias_f16 = codes.data_ptr(), scale.data_ptr(), bias.data_ptr()
+    with torch.cuda.device(device):
+        rc = lib.e4q_quantize_rowwise_greedy_batch(descs, len(tables), int(nbits), int(n_bins), float(ratio),
+                                                   _stream_ptr(stream, device))
+    _check(rc)
+    return outs
+
+
+def dequantize(codes: torch.Tensor, scale_f16: torch.Tensor, bias_f16: torch.Tensor, dim: int, nbits: int = 4,
+               out: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """e4q_dequantize: float32 [rows, dim] from packed codes and float16 scale/bias."""
+    lib = load_library()
+    if not (codes.is_cuda and scale_f16.is_cuda and bias_f16.is_cuda):
+        raise ValueError("libe4q works on device memory only")
+    if codes.dtype != torch.uint8 or scale_f16.dtype != torch.float16 or bias_f16.dtype != torch.float16:
+        raise TypeError("codes must be uint8, scale and bias float16")
+    if not (codes.is_contiguous() and scale_f16.is_contiguous() and bias_f16.is_contiguous()):
+        raise ValueError("codes, scale and bias must be dense")
+    rows = codes.shape[0]
+    if codes.shape[1] != (dim + 1) // 2 or scale_f16.numel() != rows or bias_f16.numel() != rows:
+        raise ValueError("shapes of codes / scale / bias do not match dim")
+    if out is None:
+        out = torch.empty((rows, dim), dtype=torch.float32, device=codes.device)
+    elif out.dtype != torch.float32 or not out.is_contiguous() or tuple(out.shape) != (rows, dim):
+        raise ValueError("out must be a dense float32 [rows, dim] tensor")
+    with torch.cuda.device(codes.device):
+        rc = lib.e4q_dequantize(codes.data_ptr(), scale_f16.data_ptr(), bias_f16.data_ptr(), rows, int(dim),
+                                int(nbits), out.data_ptr(), _stream_ptr(stream, codes.device))
+    _check(rc)
+    return out

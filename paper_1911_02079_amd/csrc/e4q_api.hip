@@ -1,0 +1,155 @@
+// C ABI of libe4q (see include/e4q.h for the contract of every entry point).
+// Host code only: argument validation, choice of kernel, launch on the caller's stream.
+#include "../../include/e4q.h"
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+
+#include "e4q_launch.h"
+
+namespace {
+
+thread_local char g_hip_error[256] = "";
+
+int fail_launch(hipError_t err)
+{
+    std::snprintf(g_hip_error, sizeof(g_hip_error), "%s: %s", hipGetErrorName(err), hipGetErrorString(err));
+    return E4Q_ERR_LAUNCH;
+}
+
+inline bool aligned(const void* p, size_t a) { return reinterpret_cast<uintptr_t>(p) % a == 0; }
+
+int validate_search(int32_t nbits, int32_t n_bins, float ratio)
+{
+    if (nbits != 4) return E4Q_ERR_BAD_NBITS;
+    if (n_bins < 1 || !(ratio >= 0.0f && ratio < 1.0f)) return E4Q_ERR_BAD_SEARCH;
+    return E4Q_OK;
+}
+
+int validate_table(const void* table, int dtype, int64_t rows, int32_t dim, int64_t row_stride,
+                   const uint8_t* codes, const uint16_t* scale_f16, const uint16_t* bias_f16)
+{
+    if (dtype != E4Q_F32 && dtype != E4Q_F16) return E4Q_ERR_BAD_DTYPE;
+    if (rows < 0 || dim <= 0 || dim > E4Q_MAX_DIM || row_stride < dim) return E4Q_ERR_BAD_SHAPE;
+    if (rows == 0) return E4Q_OK;
+    if (!table || !codes || !scale_f16 || !bias_f16) return E4Q_ERR_NULL_POINTER;
+    if (!aligned(table, dtype == E4Q_F32 ? 4 : 2) || !aligned(scale_f16, 2) || !aligned(bias_f16, 2))
+        return E4Q_ERR_BAD_ALIGNMENT;
+    return E4Q_OK;
+}
+
+int enqueue_greedy(const void* table, int dtype, int64_t rows, int32_t dim, int64_t row_stride,
+                   int32_t n_bins, int32_t n_iter, uint8_t* codes, uint16_t* scale_f16,
+                   uint16_t* bias_f16, hipStream_t stream)
+{
+    if (rows == 0) return E4Q_OK;
+    const size_t esz = dtype == E4Q_F32 ? 4 : 2;
+    e4q::GreedyArgs a;
+    a.table = table;
+    a.rows = rows;
+    a.row_stride = row_stride;
+    a.n_iter = n_iter;
+    a.n_bins = (float)n_bins;
+    a.codes = codes;
+    a.scale_f16 = scale_f16;
+    a.bias_f16 = bias_f16;
+    a.vec_loads = (aligned(table, 16) && (row_stride * esz) % 16 == 0) ? 1u : 0u;
+    a.vec_stores = aligned(codes, 16) ? 2u : (aligned(codes, 4) ? 1u : 0u);
+
+    hipError_t err;
+    // One row per lane needs rows/64 waves; below a few waves per SIMD that leaves most of the
+    // chip idle, but it is still the cheapest way to do the arithmetic, so it is used whenever
+    // the dimension has an instantiation.
+    if (e4q::rpl_supports_dim(dim) && (rows + 63) / 64 <= 0x7fffffffLL) {
+        err = dtype == E4Q_F32 ? e4q::launch_greedy_rpl_f32(a, dim, stream)
+                               : e4q::launch_greedy_rpl_f16(a, dim, stream);
+    } else {
+        err = e4q::launch_greedy_generic(a, dtype, dim, stream);
+    }
+    return err == hipSuccess ? E4Q_OK : fail_launch(err);
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t e4q_greedy_iterations(int32_t n_bins, float ratio)
+{
+    if (n_bins < 1 || !(ratio >= 0.0f && ratio < 1.0f)) return E4Q_ERR_BAD_SEARCH;
+    const double br = (double)n_bins * (double)ratio;
+    double t = std::ceil(br - br * 0x1p-22);
+    if (t < 0.0) t = 0.0;
+    if (t > (double)(n_bins - 1)) t = (double)(n_bins - 1);
+    return (int32_t)t;
+}
+
+int e4q_quantize_rowwise_greedy(const void* table, int dtype, int64_t rows, int32_t dim,
+                                int64_t row_stride, int32_t nbits, int32_t n_bins, float ratio,
+                                uint8_t* codes, uint16_t* scale_f16, uint16_t* bias_f16,
+                                void* hip_stream)
+{
+    int rc = validate_search(nbits, n_bins, ratio);
+    if (rc != E4Q_OK) return rc;
+    rc = validate_table(table, dtype, rows, dim, row_stride, codes, scale_f16, bias_f16);
+    if (rc != E4Q_OK) return rc;
+    return enqueue_greedy(table, dtype, rows, dim, row_stride, n_bins, e4q_greedy_iterations(n_bins, ratio),
+                          codes, scale_f16, bias_f16, static_cast<hipStream_t>(hip_stream));
+}
+
+int e4q_quantize_rowwise_greedy_batch(const e4q_table_desc* descs, int32_t n_tables, int32_t nbits,
+                                      int32_t n_bins, float ratio, void* hip_stream)
+{
+    int rc = validate_search(nbits, n_bins, ratio);
+    if (rc != E4Q_OK) return rc;
+    if (n_tables < 0) return E4Q_ERR_BAD_SHAPE;
+    if (n_tables == 0) return E4Q_OK;
+    if (!descs) return E4Q_ERR_NULL_POINTER;
+    for (int32_t t = 0; t < n_tables; ++t) {
+        const e4q_table_desc& d = descs[t];
+        rc = validate_table(d.table, d.dtype, d.rows, d.dim, d.row_stride, d.codes, d.scale_f16, d.bias_f16);
+        if (rc != E4Q_OK) return rc;
+    }
+    const int32_t n_iter = e4q_greedy_iterations(n_bins, ratio);
+    for (int32_t t = 0; t < n_tables; ++t) {
+        const e4q_table_desc& d = descs[t];
+        rc = enqueue_greedy(d.table, d.dtype, d.rows, d.dim, d.row_stride, n_bins, n_iter, d.codes,
+                            d.scale_f16, d.bias_f16, static_cast<hipStream_t>(hip_stream));
+        if (rc != E4Q_OK) return rc;
+    }
+    return E4Q_OK;
+}
+
+int e4q_dequantize(const uint8_t* codes, const uint16_t* scale_f16, const uint16_t* bias_f16,
+                   int64_t rows, int32_t dim, int32_t nbits, float* out, void* hip_stream)
+{
+    if (nbits != 4) return E4Q_ERR_BAD_NBITS;
+    if (rows < 0 || dim <= 0 || dim > E4Q_MAX_DIM) return E4Q_ERR_BAD_SHAPE;
+    if (rows == 0) return E4Q_OK;
+    if (!codes || !scale_f16 || !bias_f16 || !out) return E4Q_ERR_NULL_POINTER;
+    if (!aligned(scale_f16, 2) || !aligned(bias_f16, 2) || !aligned(out, 4)) return E4Q_ERR_BAD_ALIGNMENT;
+    const hipError_t err = e4q::launch_dequantize(codes, scale_f16, bias_f16, rows, dim, out,
+                                                  static_cast<hipStream_t>(hip_stream));
+    return err == hipSuccess ? E4Q_OK : fail_launch(err);
+}
+
+const char* e4q_strerror(int code)
+{
+    switch (code) {
+        case E4Q_OK: return "success";
+        case E4Q_ERR_NULL_POINTER: return "a required pointer is NULL";
+        case E4Q_ERR_BAD_SHAPE: return "bad shape: need rows >= 0, 0 < dim <= 4096, row_stride >= dim";
+        case E4Q_ERR_BAD_NBITS: return "nbits must be 4";
+        case E4Q_ERR_BAD_SEARCH: return "bad search parameters: need n_bins >= 1, 0 <= ratio < 1, lloyd_iters >= 0";
+        case E4Q_ERR_BAD_DTYPE: return "dtype must be E4Q_F32 (0) or E4Q_F16 (1)";
+        case E4Q_ERR_LAUNCH: return "HIP reported an error at kernel launch (see e4q_last_hip_error)";
+        case E4Q_ERR_BAD_ALIGNMENT: return "a pointer is not aligned to its element size";
+        default: return "unknown e4q error code";
+    }
+}
+
+const char* e4q_last_hip_error(void) { return g_hip_error; }
+
+int e4q_version(void) { return 100; }  // 0.1.0
+
+}  // extern "C"

@@ -1,0 +1,33 @@
+// Host-visible launch interface between the C ABI (e4q_api.hip) and the kernel translation units.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace e4q {
+
+// Arguments of every greedy-search kernel.  Pointers are device pointers.
+struct GreedyArgs {
+    const void* table;
+    int64_t rows;
+    int64_t row_stride;  // elements between rows
+    int32_t n_iter;      // trips of Algorithm 1's loop (two candidate ranges per trip)
+    float n_bins;        // b of Algorithm 1 as a float (divisor of the step size)
+    uint8_t* codes;
+    uint16_t* scale_f16;
+    uint16_t* bias_f16;
+    uint32_t vec_loads;   // 1: table base and row pitch are 16-byte aligned
+    uint32_t vec_stores;  // 0: byte stores, 1: codes base 4-byte aligned, 2: 16-byte aligned
+};
+
+// Register-resident kernels exist for these dimensions (multiples of 8 up to 128).
+inline bool rpl_supports_dim(int32_t dim) { return dim >= 8 && dim <= 128 && dim % 8 == 0; }
+
+// Each returns hipGetLastError() after enqueueing.
+hipError_t launch_greedy_rpl_f32(const GreedyArgs& a, int32_t dim, hipStream_t stream);
+hipError_t launch_greedy_rpl_f16(const GreedyArgs& a, int32_t dim, hipStream_t stream);
+hipError_t launch_greedy_generic(const GreedyArgs& a, int dtype, int32_t dim, hipStream_t stream);
+hipError_t launch_dequantize(const uint8_t* codes, const uint16_t* scale_f16, const uint16_t* bias_f16,
+                             int64_t rows, int32_t dim, float* out, hipStream_t stream);
+
+}  // namespace e4q

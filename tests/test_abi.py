@@ -1,0 +1,124 @@
+"""The C-ABI library loads without a GPU and exports every symbol that include/e4q.h declares;
+host-only entry points and argument validation behave as documented (no kernel is launched)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "e4q.h")
+
+
+@pytest.fixture(scope="module")
+def lib():
+    from paper_1911_02079_amd import binding
+
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_1911_02079_amd import build
+
+        build.build_library()
+    return binding.load_library()
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(e4q_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_header_declares_the_expected_entry_points():
+    names = declared_functions()
+    for must in ["e4q_quantize_rowwise_greedy", "e4q_dequantize", "e4q_quantize_rowwise_greedy_batch",
+                 "e4q_greedy_iterations", "e4q_strerror", "e4q_last_hip_error", "e4q_version"]:
+        assert must in names
+
+
+def test_every_declared_symbol_is_exported(lib):
+    for name in declared_functions():
+        assert hasattr(lib, name), f"{name} is declared in e4q.h but not exported by libe4q.so"
+
+
+def test_version_and_strerror(lib):
+    assert lib.e4q_version() >= 100
+    for code in range(0, -8, -1):
+        assert lib.e4q_strerror(code)
+    assert b"unknown" in lib.e4q_strerror(-99)
+    assert lib.e4q_last_hip_error() == b""
+
+
+def test_greedy_iterations_host_helper(lib):
+    assert lib.e4q_greedy_iterations(200, 0.16) == 32
+    assert lib.e4q_greedy_iterations(100, 0.16) == 16
+    assert lib.e4q_greedy_iterations(1000, 0.5) == 500
+    assert lib.e4q_greedy_iterations(20, 0.4) == 8
+    assert lib.e4q_greedy_iterations(200, 0.0) == 0
+    assert lib.e4q_greedy_iterations(3, 0.999) == 2
+    assert lib.e4q_greedy_iterations(0, 0.1) == -4
+    assert lib.e4q_greedy_iterations(10, 1.0) == -4
+    assert lib.e4q_greedy_iterations(10, float("nan")) == -4
+
+
+def test_greedy_iterations_agrees_with_the_oracles_own_formula(lib, oracle_lib):
+    for b in [1, 2, 7, 20, 100, 200, 1000, 4096]:
+        for r in [0.0, 0.01, 0.16, 0.25, 0.4, 0.5, 0.75, 0.99]:
+            assert lib.e4q_greedy_iterations(b, r) == oracle_lib.n_iter(b, r)
+
+
+def test_validation_rejects_bad_arguments_before_any_launch(lib):
+    """All of these return before touching the device, so they are safe without a GPU.
+    Pointers are fake non-NULL values that are never dereferenced on a validation error."""
+    p = ctypes.c_void_p(0x1000)
+    q = lib.e4q_quantize_rowwise_greedy
+    ok_args = dict(table=p, dtype=0, rows=10, dim=64, stride=64, nbits=4, n_bins=200, ratio=0.16,
+                   codes=p, scale=p, bias=p)
+
+    def call(**kw):
+        a = dict(ok_args, **kw)
+        return q(a["table"], a["dtype"], a["rows"], a["dim"], a["stride"], a["nbits"], a["n_bins"], a["ratio"],
+                 a["codes"], a["scale"], a["bias"], None)
+
+    assert call(nbits=8) == -3
+    assert call(n_bins=0) == -4
+    assert call(ratio=1.0) == -4
+    assert call(ratio=-0.1) == -4
+    assert call(dtype=2) == -5
+    assert call(rows=-1) == -2
+    assert call(dim=0) == -2
+    assert call(dim=4097) == -2
+    assert call(stride=63) == -2
+    assert call(table=None) == -1
+    assert call(codes=None) == -1
+    assert call(scale=None) == -1
+    assert call(bias=None) == -1
+    assert call(table=ctypes.c_void_p(0x1002)) == -7
+    assert call(rows=0, table=None, codes=None, scale=None, bias=None) == 0  # empty table: no-op
+
+    dq = lib.e4q_dequantize
+    assert dq(p, p, p, 10, 64, 8, p, None) == -3
+    assert dq(p, p, p, -1, 64, 4, p, None) == -2
+    assert dq(p, p, p, 10, 0, 4, p, None) == -2
+    assert dq(None, p, p, 10, 64, 4, p, None) == -1
+    assert dq(p, p, p, 10, 64, 4, None, None) == -1
+    assert dq(None, None, None, 0, 64, 4, None, None) == 0
+
+    from paper_1911_02079_amd.binding import TableDesc
+
+    descs = (TableDesc * 2)()
+    for d in descs:
+        d.table, d.dtype, d.dim, d.rows, d.row_stride = 0x1000, 1, 32, 5, 32
+        d.codes, d.scale_f16, d.bias_f16 = 0x1000, 0x1000, 0x1000
+    descs[1].dim = 0
+    assert lib.e4q_quantize_rowwise_greedy_batch(descs, 2, 4, 100, 0.16, None) == -2
+    assert lib.e4q_quantize_rowwise_greedy_batch(descs, 0, 4, 100, 0.16, None) == 0
+    assert lib.e4q_quantize_rowwise_greedy_batch(None, 2, 4, 100, 0.16, None) == -1
+    assert lib.e4q_quantize_rowwise_greedy_batch(descs, 2, 3, 100, 0.16, None) == -3
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+
+    import paper_1911_02079_amd as e4q
+
+    with pytest.raises(ValueError):
+        e4q.quantize_rowwise_greedy(torch.zeros(4, 8))

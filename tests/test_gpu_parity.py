@@ -1,0 +1,266 @@
+"""GPU parity: libe4q (through its C ABI, via the ctypes binding) against the CPU oracle,
+element by element on the same seeded inputs.
+
+Bar (integer outputs): packed codes, scale bits and bias bits are compared for exact equality
+on every row -- both sides follow the same binary32 operation sequence, so any difference is a
+bug, not noise.  The relative per-row l2 error (float64, from the emitted artefacts) is also
+compared at 1e-5, which is the stated tolerance for the floating-point side.
+"""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+L2_RTOL = 1e-5
+
+
+def say(msg):
+    print(f"[gpu-case] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def e4q():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    import paper_1911_02079_amd as pkg
+
+    pkg.binding.load_library()  # fails loudly if libe4q.so is missing
+    return pkg
+
+
+def row_l2(table_f32, xh):
+    return ((table_f32.astype(np.float64) - xh.astype(np.float64)) ** 2).sum(axis=1)
+
+
+def compare_with_oracle(e4q, oracle, table_gpu, n_bins, ratio, label):
+    """Quantize on the GPU and on the CPU, compare everything; returns the GPU outputs."""
+    say(f"{label}: shape={tuple(table_gpu.shape)} dtype={table_gpu.dtype} b={n_bins} r={ratio}")
+    codes, scale, bias = e4q.quantize_rowwise_greedy(table_gpu, n_bins, ratio)
+    torch.cuda.synchronize()
+    host = table_gpu.cpu().numpy()
+    o_codes, o_scale, o_bias = oracle.quantize_rowwise_greedy(np.ascontiguousarray(host), n_bins, ratio)
+    g_codes = codes.cpu().numpy()
+    g_scale = scale.cpu().view(torch.int16).numpy().view(np.uint16)
+    g_bias = bias.cpu().view(torch.int16).numpy().view(np.uint16)
+    bad_rows = np.flatnonzero((g_codes != o_codes).any(axis=1) | (g_scale != o_scale) | (g_bias != o_bias))
+    assert bad_rows.size == 0, f"{label}: {bad_rows.size} rows differ, first {bad_rows[:5]}"
+    # floating-point side of the bar: per-row l2 error of the artefacts, and the dequantizer itself
+    dim = host.shape[1]
+    xh_gpu = e4q.dequantize(codes, scale, bias, dim)
+    torch.cuda.synchronize()
+    xh_gpu = xh_gpu.cpu().numpy()
+    xh_cpu = oracle.dequantize(o_codes, o_scale, o_bias, dim)
+    assert np.array_equal(xh_gpu.view(np.uint32), xh_cpu.view(np.uint32)), f"{label}: dequantize differs"
+    f32 = host.astype(np.float32)
+    lg, lc = row_l2(f32, xh_gpu), row_l2(f32, xh_cpu)
+    assert np.all(np.abs(lg - lc) <= L2_RTOL * np.maximum(lc, 1e-300))
+    return codes, scale, bias
+
+
+# --------------------------------------------------------------------------------------------
+# The paper-shaped workloads at sizes the oracle finishes in seconds (several tiles + ragged tail)
+# --------------------------------------------------------------------------------------------
+def test_config1_gaussian_10k_x_64(e4q, oracle_lib):
+    from paper_1911_02079_amd import synth
+
+    t = synth.gaussian_table(10_000, 64, 0.1, device="cuda")
+    compare_with_oracle(e4q, oracle_lib, t, 200, 0.16, "config1")
+
+
+def test_config2_outlier_rows(e4q, oracle_lib):
+    from paper_1911_02079_amd import synth
+
+    t = synth.outlier_table(50_003, 64, device="cuda")
+    compare_with_oracle(e4q, oracle_lib, t, 200, 0.16, "config2-reduced")
+
+
+def test_config3_laplace_offset_rows(e4q, oracle_lib):
+    from paper_1911_02079_amd import synth
+
+    t = synth.laplace_offset_table(30_011, 128, device="cuda")
+    compare_with_oracle(e4q, oracle_lib, t, 200, 0.16, "config3-reduced")
+
+
+def test_config4_batch_of_half_tables(e4q, oracle_lib):
+    from paper_1911_02079_amd import synth
+
+    specs = synth.batch_specs(26, max_rows=20_000, min_rows=100)
+    tables = synth.batch_tables(specs, device="cuda")
+    say(f"config4-reduced: {len(tables)} fp16 tables, rows {[s.rows for s in specs]}")
+    outs = e4q.quantize_rowwise_greedy_batch(tables, 100, 0.16)
+    torch.cuda.synchronize()
+    for k, (t, (codes, scale, bias)) in enumerate(zip(tables, outs)):
+        o_codes, o_scale, o_bias = oracle_lib.quantize_rowwise_greedy(t.cpu().numpy(), 100, 0.16)
+        assert np.array_equal(codes.cpu().numpy(), o_codes), f"table {k}"
+        assert np.array_equal(scale.cpu().view(torch.int16).numpy().view(np.uint16), o_scale), f"table {k}"
+        assert np.array_equal(bias.cpu().view(torch.int16).numpy().view(np.uint16), o_bias), f"table {k}"
+
+
+# --------------------------------------------------------------------------------------------
+# Every register-resident dimension, both input types, ragged row counts; and the LDS fallback
+# --------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", [torch.float32, torch.float16])
+@pytest.mark.parametrize("dim", list(range(8, 129, 8)))
+def test_every_fast_dimension(e4q, oracle_lib, dim, dtype):
+    from paper_1911_02079_amd import synth
+
+    t = synth.outlier_table(64 * 5 + 17, dim, seed=1000 + dim, device="cuda").to(dtype)
+    compare_with_oracle(e4q, oracle_lib, t, 200, 0.16, f"fast dim={dim}")
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.float16])
+@pytest.mark.parametrize("dim", [1, 2, 3, 5, 7, 12, 33, 63, 100, 130, 200, 256, 257, 1000])
+def test_fallback_dimensions(e4q, oracle_lib, dim, dtype):
+    from paper_1911_02079_amd import synth
+
+    t = synth.outlier_table(131, dim, seed=2000 + dim, device="cuda").to(dtype)
+    compare_with_oracle(e4q, oracle_lib, t, 50, 0.3, f"fallback dim={dim}")
+
+
+def test_largest_dimension(e4q, oracle_lib):
+    from paper_1911_02079_amd import synth
+
+    t = synth.gaussian_table(9, 4096, 0.1, seed=7, device="cuda")
+    compare_with_oracle(e4q, oracle_lib, t, 20, 0.25, "dim=4096")
+
+
+# --------------------------------------------------------------------------------------------
+# Search settings: ASYM (r = 0), b = 100, "GREEDY (opt)" b = 1000, r = 0.5, tiny b
+# --------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("n_bins,ratio", [(200, 0.0), (100, 0.16), (1000, 0.5), (1, 0.5), (2, 0.9), (37, 0.33)])
+def test_search_settings(e4q, oracle_lib, n_bins, ratio):
+    from paper_1911_02079_amd import synth
+
+    t = synth.outlier_table(1_031, 64, seed=77, device="cuda")
+    compare_with_oracle(e4q, oracle_lib, t, n_bins, ratio, "settings")
+
+
+def test_greedy_never_worse_than_minmax_on_the_gpu(e4q):
+    from paper_1911_02079_amd import synth
+
+    t = synth.outlier_table(20_000, 64, seed=5, device="cuda")
+    say("invariant: greedy <= asym")
+    a = e4q.dequantize(*e4q.quantize_rowwise_greedy(t, 200, 0.0), 64)
+    g = e4q.dequantize(*e4q.quantize_rowwise_greedy(t, 200, 0.16), 64)
+    la = ((t.double() - a.double()) ** 2).sum(1)
+    lg = ((t.double() - g.double()) ** 2).sum(1)
+    assert bool((lg <= la * (1 + 1e-6)).all())
+    assert float(lg.sum() / la.sum()) < 0.9  # clipping pays on outlier rows
+
+
+# --------------------------------------------------------------------------------------------
+# Edge cases
+# --------------------------------------------------------------------------------------------
+def test_empty_and_single_row(e4q, oracle_lib):
+    say("empty table")
+    t = torch.empty((0, 64), device="cuda")
+    codes, scale, bias = e4q.quantize_rowwise_greedy(t)
+    assert codes.shape == (0, 32) and scale.shape == (0,)
+    assert e4q.dequantize(codes, scale, bias, 64).shape == (0, 64)
+    for dim in (64, 13):
+        compare_with_oracle(e4q, oracle_lib, torch.randn(1, dim, device="cuda"), 200, 0.16, "one row")
+
+
+def test_degenerate_rows(e4q, oracle_lib):
+    t = torch.zeros((70, 16), device="cuda")
+    t[1] = 0.375
+    t[2] = -7.0
+    t[3] = 1.0
+    t[3, 4] = 1.0 + 2.0 ** -23          # range far below binary16 resolution: scale rounds to 0
+    t[4, :8] = 1.0                       # two-valued row
+    t[5] = torch.arange(16, device="cuda") * 0.25 - 2.0  # exact 16-point grid
+    t[6] = 6.0e-8                        # binary16 subnormal bias
+    t[7, 0] = 1.0e-7
+    t[8:] = torch.randn(62, 16, device="cuda") * 1e-6    # tiny values: subnormal scale
+    codes, scale, bias = compare_with_oracle(e4q, oracle_lib, t, 200, 0.16, "degenerate f32")
+    assert int(codes[:4].sum()) == 0
+    xh = e4q.dequantize(codes, scale, bias, 16)
+    assert torch.equal(xh[5], t[5])      # Eq. 1 reproduces a row that lies on a 16-point grid
+    compare_with_oracle(e4q, oracle_lib, t[:, :13].contiguous(), 200, 0.16, "degenerate generic")
+
+
+def test_strided_and_unaligned_views(e4q, oracle_lib):
+    from paper_1911_02079_amd import synth
+
+    big = synth.gaussian_table(300, 100, 0.1, seed=3, device="cuda")
+    say("row stride > dim (column slice of a wider table)")
+    view = big[:, :64]                    # stride 100 elements: rows are 16-byte aligned only by luck
+    assert view.stride(0) == 100
+    codes, scale, bias = e4q.quantize_rowwise_greedy(view)
+    torch.cuda.synchronize()
+    o = oracle_lib.quantize_rowwise_greedy(np.ascontiguousarray(view.cpu().numpy()))
+    assert np.array_equal(codes.cpu().numpy(), o[0])
+    say("base pointer offset by one element (4-byte aligned only)")
+    flat = synth.gaussian_table(1, 64 * 200 + 1, 0.1, seed=4, device="cuda").reshape(-1)
+    off = flat[1:].reshape(200, 64)
+    assert off.data_ptr() % 16 != 0
+    codes, scale, bias = e4q.quantize_rowwise_greedy(off)
+    torch.cuda.synchronize()
+    o = oracle_lib.quantize_rowwise_greedy(np.ascontiguousarray(off.cpu().numpy()))
+    assert np.array_equal(codes.cpu().numpy(), o[0])
+    assert np.array_equal(scale.cpu().view(torch.int16).numpy().view(np.uint16), o[1])
+    say("outputs at odd byte offsets")
+    rows, dim = 200, 64
+    cbuf = torch.zeros(rows * 32 + 1, dtype=torch.uint8, device="cuda")
+    out = (cbuf[1:].reshape(rows, 32), torch.empty(rows, dtype=torch.float16, device="cuda"),
+           torch.empty(rows, dtype=torch.float16, device="cuda"))
+    e4q.quantize_rowwise_greedy(off, out=out)
+    torch.cuda.synchronize()
+    assert np.array_equal(out[0].cpu().numpy(), o[0])
+    assert int(cbuf[0]) == 0
+    say("dequantize from an unaligned code buffer")
+    xh = e4q.dequantize(cbuf[1:].reshape(rows, 32), out[1], out[2], dim)
+    torch.cuda.synchronize()
+    assert np.array_equal(xh.cpu().numpy(), oracle_lib.dequantize(o[0], o[1], o[2], dim))
+
+
+def test_outputs_do_not_overrun(e4q):
+    """Guard bands around the outputs stay untouched (ragged row count, fast and fallback paths)."""
+    from paper_1911_02079_amd import synth
+
+    for dim in (64, 13):
+        rows = 64 * 3 + 5
+        t = synth.gaussian_table(rows, dim, 0.1, seed=9, device="cuda")
+        nb = (dim + 1) // 2
+        say(f"guard bands dim={dim}")
+        cbuf = torch.full((rows * nb + 256,), 0xA5, dtype=torch.uint8, device="cuda")
+        sbuf = torch.full((rows + 64,), -3.0, dtype=torch.float16, device="cuda")
+        bbuf = torch.full((rows + 64,), -3.0, dtype=torch.float16, device="cuda")
+        out = (cbuf[128:128 + rows * nb].reshape(rows, nb), sbuf[32:32 + rows], bbuf[32:32 + rows])
+        e4q.quantize_rowwise_greedy(t, out=out)
+        torch.cuda.synchronize()
+        assert bool((cbuf[:128] == 0xA5).all()) and bool((cbuf[128 + rows * nb:] == 0xA5).all())
+        for buf in (sbuf, bbuf):
+            assert bool((buf[:32] == -3.0).all()) and bool((buf[32 + rows:] == -3.0).all())
+        xbuf = torch.full((rows * dim + 64,), 7.0, device="cuda")
+        e4q.dequantize(*out, dim, out=xbuf[32:32 + rows * dim].reshape(rows, dim))
+        torch.cuda.synchronize()
+        assert bool((xbuf[:32] == 7.0).all()) and bool((xbuf[32 + rows * dim:] == 7.0).all())
+
+
+def test_runs_on_a_side_stream(e4q, oracle_lib):
+    from paper_1911_02079_amd import synth
+
+    t = synth.gaussian_table(5_000, 32, 0.1, seed=12, device="cuda")
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    say("side stream")
+    with torch.cuda.stream(s):
+        codes, scale, bias = e4q.quantize_rowwise_greedy(t)
+        xh = e4q.dequantize(codes, scale, bias, 32)
+    s.synchronize()
+    o = oracle_lib.quantize_rowwise_greedy(t.cpu().numpy())
+    assert np.array_equal(codes.cpu().numpy(), o[0])
+    assert np.array_equal(xh.cpu().numpy(), oracle_lib.dequantize(*o, 32))
+
+
+def test_binding_reports_library_errors(e4q):
+    t = torch.randn(4, 64, device="cuda")
+    with pytest.raises(e4q.E4QError) as ei:
+        e4q.quantize_rowwise_greedy(t, nbits=8)
+    assert ei.value.code == -3
+    with pytest.raises(e4q.E4QError):
+        e4q.quantize_rowwise_greedy(t, ratio=1.5)

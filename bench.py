@@ -77,7 +77,7 @@ def cpu_baseline(table_gpu, n_bins: int, ratio: float, target_seconds: float = 1
     t0 = time.perf_counter()
     oracle.quantize_rowwise_greedy(probe, n_bins, ratio)
     per_row = (time.perf_counter() - t0) / probe.shape[0]
-    sample_rows = int(min(rows, max(cores * 64, target_seconds * cores / per_row)))
+    sample_rows = int(min(rows, 4_000_000, max(cores * 64, target_seconds * cores / per_row)))
     sample = np.ascontiguousarray(table_gpu[:sample_rows].cpu().numpy())
     bounds = [sample_rows * k // cores for k in range(cores + 1)]
     t0 = time.perf_counter()
@@ -97,6 +97,9 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="laplace_10M_x_128", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device-to-device copy kernel three times, so that a "
+                         "rocprofv3 --pmc run can scale FETCH_SIZE / WRITE_SIZE by a kernel of known traffic")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only: this build has no multi-GPU path (rows shard with no "
@@ -142,6 +145,14 @@ def main() -> int:
         step(evs[k])
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=table.device)  # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)  # one elementwise copy kernel: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     ms_per_step = 1e3 * elapsed / args.steps
     greedy_ms = sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps

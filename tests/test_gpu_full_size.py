@@ -1,0 +1,106 @@
+"""Parity at the full sizes of the benchmark configurations, in the launch configuration that
+bench.py times (whole table in one call, outputs preallocated).
+
+The oracle is fast enough (about 10 us per 128-wide row and core) that every row of every
+configuration is compared, not a sample: the host threads split the rows.  Properties that hold
+at any size (code range, extremes of each row, never worse than min/max) are checked on the GPU
+over all rows as well.
+"""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from helpers import f16_bits, oracle_rows_in_parallel
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(f"[gpu-case] {msg}", flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def e4q():
+    assert torch.cuda.is_available()
+    import paper_1911_02079_amd as pkg
+
+    pkg.binding.load_library()
+    return pkg
+
+
+def full_compare(e4q, oracle, table, n_bins, ratio, label):
+    rows, dim = table.shape
+    say(f"{label}: GPU quantize {rows} x {dim}")
+    out = e4q.alloc_outputs(rows, dim, table.device)
+    e4q.quantize_rowwise_greedy(table, n_bins, ratio, out=out)
+    torch.cuda.synchronize()
+    say(f"{label}: oracle on all rows")
+    o_codes, o_scale, o_bias = oracle_rows_in_parallel(oracle, table.cpu().numpy(), n_bins, ratio)
+    say(f"{label}: compare")
+    bad = np.flatnonzero((out[0].cpu().numpy() != o_codes).any(axis=1) | (f16_bits(out[1]) != o_scale) |
+                         (f16_bits(out[2]) != o_bias))
+    assert bad.size == 0, f"{label}: {bad.size} of {rows} rows differ, first {bad[:5]}"
+    return out
+
+
+def gpu_properties(e4q, table, out, n_bins, chunk=1 << 20):
+    """Code range / extremes / never-worse-than-min-max over all rows, evaluated with torch on the GPU."""
+    rows, dim = table.shape
+    codes, scale, bias = out
+    asym = e4q.quantize_rowwise_greedy(table, n_bins, 0.0)
+    xh = e4q.dequantize(codes, scale, bias, dim)
+    xa = e4q.dequantize(*asym, dim)
+    worse = 0
+    for r0 in range(0, rows, chunk):
+        sl = slice(r0, min(rows, r0 + chunk))
+        t = table[sl].double()
+        lg = ((t - xh[sl].double()) ** 2).sum(1)
+        la = ((t - xa[sl].double()) ** 2).sum(1)
+        worse += int((lg > la * (1 + 1e-6)).sum())
+        c = codes[sl]
+        lo_n, hi_n = c & 0xF, c >> 4
+        q = torch.stack([lo_n, hi_n], dim=2).reshape(c.shape[0], -1)[:, :dim]
+        idx = torch.arange(c.shape[0], device=c.device)
+        nonconst = scale[sl] != 0
+        assert bool((q[idx, table[sl].argmin(1)][nonconst] == 0).all())
+        assert bool((q[idx, table[sl].argmax(1)][nonconst] == 15).all())
+    assert worse == 0
+
+
+def test_full_config2_outlier_1M_x_64(e4q, oracle_lib):
+    from paper_1911_02079_amd import synth
+
+    t = synth.outlier_table(1_000_000, 64, device="cuda")
+    out = full_compare(e4q, oracle_lib, t, 200, 0.16, "config2")
+    gpu_properties(e4q, t, out, 200)
+
+
+def test_full_config3_laplace_10M_x_128(e4q, oracle_lib):
+    from paper_1911_02079_amd import synth
+
+    t = synth.laplace_offset_table(10_000_000, 128, device="cuda")
+    out = full_compare(e4q, oracle_lib, t, 200, 0.16, "config3")
+    gpu_properties(e4q, t, out, 200)
+    say("config3: dequantize against the oracle on a strided sample of rows")
+    idx = torch.arange(0, 10_000_000, 997, device="cuda")
+    xh = e4q.dequantize(*out, 128)[idx].cpu().numpy()
+    want = oracle_lib.dequantize(out[0][idx].cpu().numpy(), f16_bits(out[1][idx]), f16_bits(out[2][idx]), 128)
+    assert np.array_equal(xh, want)
+
+
+def test_full_config4_batch_of_26_half_tables(e4q, oracle_lib):
+    from paper_1911_02079_amd import synth
+
+    specs = synth.batch_specs()
+    say(f"config4: drawing {len(specs)} fp16 tables, {sum(s.rows for s in specs)} rows in total")
+    tables = synth.batch_tables(specs, device="cuda")
+    outs = e4q.quantize_rowwise_greedy_batch(tables, 100, 0.16)
+    torch.cuda.synchronize()
+    for k, (t, out) in enumerate(zip(tables, outs)):
+        say(f"config4: table {k} {tuple(t.shape)}")
+        o_codes, o_scale, o_bias = oracle_rows_in_parallel(oracle_lib, t.cpu().numpy(), 100, 0.16)
+        assert np.array_equal(out[0].cpu().numpy(), o_codes), f"table {k}"
+        assert np.array_equal(f16_bits(out[1]), o_scale) and np.array_equal(f16_bits(out[2]), o_bias), f"table {k}"

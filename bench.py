@@ -181,7 +181,7 @@ def main() -> int:
         "kernels": {
             "greedy_rpl_kernel": {"avg_ms": greedy_ms, "rows_per_s": rows / (greedy_ms * 1e-3),
                                   "algorithmic_GBps": q_bytes / (greedy_ms * 1e-3) / 1e9},
-            "dequantize_w8_kernel": {"avg_ms": dequant_ms, "algorithmic_GBps": dq_bytes / (dequant_ms * 1e-3) / 1e9,
+            "dequantize_w4_kernel": {"avg_ms": dequant_ms, "algorithmic_GBps": dq_bytes / (dequant_ms * 1e-3) / 1e9,
                                      "frac_of_hbm_peak": dq_bytes / (dequant_ms * 1e-3) / PEAK_HBM_BYTES},
         },
         "roofline": {

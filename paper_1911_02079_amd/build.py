@@ -20,7 +20,8 @@ OBJ_DIR = os.path.join(HERE, "_build")
 LIB_PATH = os.path.join(HERE, "libe4q.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
-SOURCES = ["e4q_api.hip", "greedy_rpl_f32.hip", "greedy_rpl_f16.hip", "greedy_generic.hip", "dequantize.hip"]
+SOURCES = ["e4q_api.hip", "greedy_rpl_f32.hip", "greedy_rpl_f16.hip", "greedy_swl_f32_small.hip",
+           "greedy_swl_f32_big.hip", "greedy_swl_f16_small.hip", "greedy_swl_f16_big.hip", "dequantize.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

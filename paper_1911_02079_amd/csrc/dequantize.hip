@@ -1,8 +1,6 @@
 // De-quantization x_float = scale * x_int + bias (the sentence after Eq. 1).
 //
-// Bound by HBM: d/2 + 4 bytes in, 4d bytes out per row.  The fast path gives each thread one
-// aligned 32-bit word of codes (8 elements) and lets it write two 16-byte vectors, so a wave
-// reads 256 contiguous bytes and writes 2 KiB contiguous bytes per instruction pair.
+// Bound by HBM: d/2 + 4 bytes in, 4d bytes out per row.
 #include "e4q_device.h"
 #include "e4q_launch.h"
 
@@ -11,30 +9,27 @@ namespace e4q {
 constexpr int kDqBlock = 256;
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
-// dim % 8 == 0, codes 4-byte aligned, out 16-byte aligned.  One thread per code word.
-__global__ void __launch_bounds__(kDqBlock) dequantize_w8_kernel(const uint32_t* __restrict__ codes,
+// dim % 4 == 0, codes 2-byte aligned, out 16-byte aligned.  One thread per 4 elements: a wave
+// reads 128 contiguous bytes of codes and writes 1 KiB of contiguous output per store instruction
+// (full cache lines, so nothing is written twice).
+__global__ void __launch_bounds__(kDqBlock) dequantize_w4_kernel(const uint16_t* __restrict__ codes,
                                                                 const uint16_t* __restrict__ scale_f16,
                                                                 const uint16_t* __restrict__ bias_f16,
-                                                                int64_t n_words, uint32_t words_per_row,
+                                                                int64_t n_quads, uint32_t quads_per_row,
                                                                 floatx4* __restrict__ out)
 {
     const int64_t stride = (int64_t)gridDim.x * kDqBlock;
-    for (int64_t w = (int64_t)blockIdx.x * kDqBlock + threadIdx.x; w < n_words; w += stride) {
-        const int64_t row = w / words_per_row;
+    for (int64_t w = (int64_t)blockIdx.x * kDqBlock + threadIdx.x; w < n_quads; w += stride) {
+        const int64_t row = (n_quads <= 0xffffffffLL) ? (int64_t)((uint32_t)w / quads_per_row) : w / quads_per_row;
         const float scale = f16_bits_to_float(scale_f16[row]);
         const float bias = f16_bits_to_float(bias_f16[row]);
         const uint32_t c = __builtin_nontemporal_load(codes + w);
-        floatx4 lo, hi;
-        lo.x = __builtin_fmaf((float)(c & 15u), scale, bias);
-        lo.y = __builtin_fmaf((float)((c >> 4) & 15u), scale, bias);
-        lo.z = __builtin_fmaf((float)((c >> 8) & 15u), scale, bias);
-        lo.w = __builtin_fmaf((float)((c >> 12) & 15u), scale, bias);
-        hi.x = __builtin_fmaf((float)((c >> 16) & 15u), scale, bias);
-        hi.y = __builtin_fmaf((float)((c >> 20) & 15u), scale, bias);
-        hi.z = __builtin_fmaf((float)((c >> 24) & 15u), scale, bias);
-        hi.w = __builtin_fmaf((float)(c >> 28), scale, bias);
-        __builtin_nontemporal_store(lo, out + 2 * w);
-        __builtin_nontemporal_store(hi, out + 2 * w + 1);
+        floatx4 v;
+        v.x = __builtin_fmaf((float)(c & 15u), scale, bias);
+        v.y = __builtin_fmaf((float)((c >> 4) & 15u), scale, bias);
+        v.z = __builtin_fmaf((float)((c >> 8) & 15u), scale, bias);
+        v.w = __builtin_fmaf((float)(c >> 12), scale, bias);
+        __builtin_nontemporal_store(v, out + w);
     }
 }
 
@@ -60,15 +55,15 @@ hipError_t launch_dequantize(const uint8_t* codes, const uint16_t* scale_f16, co
                              int64_t rows, int32_t dim, float* out, hipStream_t stream)
 {
     const int64_t max_blocks = 256 * 64;  // enough waves to cover the chip; the rest is a loop
-    const bool fast = dim % 8 == 0 && (reinterpret_cast<uintptr_t>(codes) % 4 == 0) &&
+    const bool fast = dim % 4 == 0 && (reinterpret_cast<uintptr_t>(codes) % 2 == 0) &&
                       (reinterpret_cast<uintptr_t>(out) % 16 == 0);
     if (fast) {
-        const int64_t n_words = rows * (dim / 8);
-        int64_t blocks = (n_words + kDqBlock - 1) / kDqBlock;
+        const int64_t n_quads = rows * (dim / 4);
+        int64_t blocks = (n_quads + kDqBlock - 1) / kDqBlock;
         if (blocks > max_blocks) blocks = max_blocks;
-        hipLaunchKernelGGL(dequantize_w8_kernel, dim3((unsigned)blocks), dim3(kDqBlock), 0, stream,
-                           reinterpret_cast<const uint32_t*>(codes), scale_f16, bias_f16, n_words,
-                           (uint32_t)(dim / 8), reinterpret_cast<floatx4*>(out));
+        hipLaunchKernelGGL(dequantize_w4_kernel, dim3((unsigned)blocks), dim3(kDqBlock), 0, stream,
+                           reinterpret_cast<const uint16_t*>(codes), scale_f16, bias_f16, n_quads,
+                           (uint32_t)(dim / 4), reinterpret_cast<floatx4*>(out));
     } else {
         const int64_t n_elems = rows * dim;
         int64_t blocks = (n_elems + kDqBlock - 1) / kDqBlock;

@@ -57,15 +57,32 @@ int enqueue_greedy(const void* table, int dtype, int64_t rows, int32_t dim, int6
     a.vec_loads = (aligned(table, 16) && (row_stride * esz) % 16 == 0) ? 1u : 0u;
     a.vec_stores = aligned(codes, 16) ? 2u : (aligned(codes, 4) ? 1u : 0u);
 
+    // Kernel choice.  One row per lane (rows/64 waves, rows in registers, ~3 % overhead over the
+    // algorithmic operation count) is the cheapest way to do the arithmetic and is used whenever the
+    // table has enough rows to occupy the chip and the dimension has an instantiation.  Otherwise a
+    // row is spread over L lanes with E contiguous elements each: E = 8 when parallelism or
+    // coalescing matters most (few rows; ratio == 0, which is bound by HBM), E up to 128 when the
+    // table is large but its dimension has no one-row-per-lane kernel.
+    const int64_t rpl_waves = (rows + 63) / 64;
+    const bool few_rows = rpl_waves < 512;  // under half a wave per SIMD
     hipError_t err;
-    // One row per lane needs rows/64 waves; below a few waves per SIMD that leaves most of the
-    // chip idle, but it is still the cheapest way to do the arithmetic, so it is used whenever
-    // the dimension has an instantiation.
-    if (e4q::rpl_supports_dim(dim) && (rows + 63) / 64 <= 0x7fffffffLL) {
+    if (e4q::rpl_supports_dim(dim) && n_iter > 0 && !few_rows) {
         err = dtype == E4Q_F32 ? e4q::launch_greedy_rpl_f32(a, dim, stream)
                                : e4q::launch_greedy_rpl_f16(a, dim, stream);
     } else {
-        err = e4q::launch_greedy_generic(a, dtype, dim, stream);
+        int E;
+        if (n_iter == 0 || few_rows)
+            E = dim <= 512 ? 8 : dim <= 1024 ? 16 : dim <= 2048 ? 32 : 64;
+        else
+            E = dim <= 8 ? 8 : dim <= 16 ? 16 : dim <= 32 ? 32 : dim <= 64 ? 64 : 128;
+        int L = 1;
+        while (E * L < dim) L *= 2;
+        if (E == 128)
+            err = dtype == E4Q_F32 ? e4q::launch_greedy_swl_f32_big(a, dim, E, L, stream)
+                                   : e4q::launch_greedy_swl_f16_big(a, dim, E, L, stream);
+        else
+            err = dtype == E4Q_F32 ? e4q::launch_greedy_swl_f32_small(a, dim, E, L, stream)
+                                   : e4q::launch_greedy_swl_f16_small(a, dim, E, L, stream);
     }
     return err == hipSuccess ? E4Q_OK : fail_launch(err);
 }

@@ -26,7 +26,12 @@ inline bool rpl_supports_dim(int32_t dim) { return dim >= 8 && dim <= 128 && dim
 // Each returns hipGetLastError() after enqueueing.
 hipError_t launch_greedy_rpl_f32(const GreedyArgs& a, int32_t dim, hipStream_t stream);
 hipError_t launch_greedy_rpl_f16(const GreedyArgs& a, int32_t dim, hipStream_t stream);
-hipError_t launch_greedy_generic(const GreedyArgs& a, int dtype, int32_t dim, hipStream_t stream);
+// Sub-wave layouts: L lanes per row, E contiguous elements per lane (see greedy_swl.h).
+// "small": E in {8, 16, 32, 64}; "big": E = 128.  Needs dim <= E * L.
+hipError_t launch_greedy_swl_f32_small(const GreedyArgs& a, int32_t dim, int E, int L, hipStream_t stream);
+hipError_t launch_greedy_swl_f32_big(const GreedyArgs& a, int32_t dim, int E, int L, hipStream_t stream);
+hipError_t launch_greedy_swl_f16_small(const GreedyArgs& a, int32_t dim, int E, int L, hipStream_t stream);
+hipError_t launch_greedy_swl_f16_big(const GreedyArgs& a, int32_t dim, int E, int L, hipStream_t stream);
 hipError_t launch_dequantize(const uint8_t* codes, const uint16_t* scale_f16, const uint16_t* bias_f16,
                              int64_t rows, int32_t dim, float* out, hipStream_t stream);
 

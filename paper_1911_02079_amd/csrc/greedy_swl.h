@@ -1,0 +1,223 @@
+// Greedy clip search with L lanes per row ("sub-wave layout"): lane j of a row's group keeps the
+// E contiguous elements [j*E, (j+1)*E) of the row in registers.
+//
+// The error sum of a range is an in-lane balanced tree over the lane's E elements followed by an
+// xor-butterfly over the L lanes of the group; with contiguous chunks per lane that is exactly the
+// balanced tree over index-adjacent pairs of the whole (zero padded) row, so results are bit
+// identical to the one-row-per-lane kernels.  All L lanes of a group end up with the same sums and
+// take the same decisions.
+//
+// Used where one row per lane is the wrong shape:
+//   * few rows (rows/64 waves would leave most of the chip idle): E = 8 spreads a row over up to
+//     64 lanes;
+//   * ratio == 0 (plain min/max quantization, bound by HBM): with E = 8 a wave reads and writes
+//     contiguous memory;
+//   * dimensions above 128 or not a multiple of 8: E = 128 keeps the per-range scalar work (two
+//     divisions, two binary16 round trips, ~45 instructions that every lane of the group repeats)
+//     small against 8 operations for each of 128 elements.
+// Masked instantiations take any dim <= E*L: elements at or beyond dim contribute exactly +0 to
+// the sums and are kept out of min/max.  MASK = 0: dim == E*L, no masking; MASK = 1: dim is a
+// multiple of 8, one select per block of 8 elements; MASK = 2: any dim, one select per element.
+#pragma once
+
+#include "e4q_device.h"
+#include "e4q_launch.h"
+
+namespace e4q {
+
+constexpr int kSwlBlock = 256;
+
+// Value of lane (id xor OFF).  DPP row operations inside 16 lanes, ds_bpermute beyond.
+template <int OFF>
+__device__ __forceinline__ float lane_xor(float v)
+{
+    const int i = __builtin_bit_cast(int, v);
+    int r;
+    if constexpr (OFF == 1) {
+        r = __builtin_amdgcn_update_dpp(i, i, 0xB1, 0xF, 0xF, false);  // quad_perm [1,0,3,2]
+    } else if constexpr (OFF == 2) {
+        r = __builtin_amdgcn_update_dpp(i, i, 0x4E, 0xF, 0xF, false);  // quad_perm [2,3,0,1]
+    } else if constexpr (OFF == 4) {
+        // row_half_mirror (lane k <-> 7-k of each 8): the partner sits in the other quad, and after
+        // the OFF = 1, 2 steps all lanes of a quad hold the same value
+        r = __builtin_amdgcn_update_dpp(i, i, 0x141, 0xF, 0xF, false);
+    } else if constexpr (OFF == 8) {
+        r = __builtin_amdgcn_update_dpp(i, i, 0x140, 0xF, 0xF, false);  // row_mirror (k <-> 15-k)
+    } else {
+        r = __shfl_xor(i, OFF, 64);
+    }
+    return __builtin_bit_cast(float, r);
+}
+
+template <int L, class Op>
+__device__ __forceinline__ float group_reduce(float v, Op op)
+{
+    if constexpr (L > 1) v = op(v, lane_xor<1>(v));
+    if constexpr (L > 2) v = op(v, lane_xor<2>(v));
+    if constexpr (L > 4) v = op(v, lane_xor<4>(v));
+    if constexpr (L > 8) v = op(v, lane_xor<8>(v));
+    if constexpr (L > 16) v = op(v, lane_xor<16>(v));
+    if constexpr (L > 32) v = op(v, lane_xor<32>(v));
+    return v;
+}
+
+template <int E, int L, int MASK>
+__device__ __forceinline__ float swl_range_loss(const float (&x)[E], int nvalid, float lo, float hi)
+{
+    const StoredParams p = stored_params(lo, hi);
+    float part;
+    if constexpr (MASK == 1) {
+        // tree over blocks of 8 of trees over 8 elements: the same balanced tree, masked per block
+        const int nblocks = nvalid / 8;
+        part = tree_sum<0, E / 8, E / 8>([&](auto b) {
+            constexpr int blk = decltype(b)::value;
+            const float bs = tree_sum<8 * blk, 8, E>([&](auto k) { return elem_sq_err(x[decltype(k)::value], p); });
+            return (blk < nblocks) ? bs : 0.0f;
+        });
+    } else {
+        part = tree_sum<0, E, E>([&](auto k) {
+            constexpr int e = decltype(k)::value;
+            const float s = elem_sq_err(x[e], p);
+            if constexpr (MASK == 2) return (e < nvalid) ? s : 0.0f;
+            else return s;
+        });
+    }
+    return group_reduce<L>(part, [](float a, float b) { return a + b; });
+}
+
+template <int E, int L, typename Tin, int MASK>
+__global__ void __launch_bounds__(kSwlBlock) greedy_swl_kernel(GreedyArgs a, int32_t d)
+{
+    constexpr bool MASKED = MASK != 0;
+    static_assert(E % 8 == 0 && (E & (E - 1)) == 0 && (L & (L - 1)) == 0 && L <= 64, "bad layout");
+    constexpr int kRowsPerBlock = kSwlBlock / L;
+    const int sub = threadIdx.x % L;
+    const int64_t row = (int64_t)blockIdx.x * kRowsPerBlock + threadIdx.x / L;
+    const bool live = row < a.rows;
+    const int64_t r = live ? row : a.rows - 1;  // tail groups redo the last row and store nothing
+    const int base = sub * E;
+    const int nvalid = MASKED ? min(max(d - base, 0), E) : E;
+
+    const Tin* src = static_cast<const Tin*>(a.table) + r * a.row_stride;
+    float x[E];
+    if constexpr (!MASKED) {
+        if (a.vec_loads) {
+            constexpr int VEC = 16 / sizeof(Tin);
+            typedef Tin vec_t __attribute__((ext_vector_type(VEC)));
+            const vec_t* v = reinterpret_cast<const vec_t*>(src + base);
+#pragma unroll
+            for (int k = 0; k < E / VEC; ++k) {
+                const vec_t t = v[k];
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) x[VEC * k + e] = (float)t[e];
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < E; ++e) x[e] = (float)src[base + e];
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < E; ++e) x[e] = (float)src[(e < nvalid) ? base + e : 0];  // pad with element 0
+    }
+
+    float lo0 = x[0], hi0 = x[0];
+#pragma unroll
+    for (int e = 1; e < E; ++e) {
+        lo0 = __builtin_fminf(lo0, x[e]);
+        hi0 = __builtin_fmaxf(hi0, x[e]);
+    }
+    lo0 = group_reduce<L>(lo0, [](float p, float q) { return __builtin_fminf(p, q); });
+    hi0 = group_reduce<L>(hi0, [](float p, float q) { return __builtin_fmaxf(p, q); });
+
+    float best_lo = lo0, best_hi = hi0;
+    if (a.n_iter > 0) {
+        const float stepsize = (hi0 - lo0) / a.n_bins;
+        float cur_lo = lo0, cur_hi = hi0;
+        float best = swl_range_loss<E, L, MASK>(x, nvalid, lo0, hi0);
+        for (int it = 0; it < a.n_iter; ++it) {
+            const float next_lo = cur_lo + stepsize;
+            const float next_hi = cur_hi - stepsize;
+            const float loss_l = swl_range_loss<E, L, MASK>(x, nvalid, next_lo, cur_hi);
+            const float loss_r = swl_range_loss<E, L, MASK>(x, nvalid, cur_lo, next_hi);
+            const bool left = loss_l < loss_r;  // a tie moves the upper bound
+            cur_lo = left ? next_lo : cur_lo;
+            cur_hi = left ? cur_hi : next_hi;
+            const float cand = left ? loss_l : loss_r;
+            const bool better = cand < best;  // strictly smaller replaces
+            best = better ? cand : best;
+            best_lo = better ? cur_lo : best_lo;
+            best_hi = better ? cur_hi : best_hi;
+        }
+    }
+
+    const float scale32 = (best_hi - best_lo) / kQMax;
+    const uint16_t scale_bits = f16_bits(scale32);
+    const uint16_t bias_bits = f16_bits(best_lo);
+    StoredParams p;
+    p.scale = f16_bits_to_float(scale_bits);
+    p.bias = f16_bits_to_float(bias_bits);
+    p.inv = (p.scale == 0.0f) ? 0.0f : 1.0f / p.scale;
+
+    constexpr int NWORDS = E / 8;
+    uint32_t w[NWORDS];
+#pragma unroll
+    for (int i = 0; i < NWORDS; ++i) {
+        uint32_t acc = 0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const uint32_t q = (uint32_t)quantize_elem(x[8 * i + e], p);
+            acc |= ((!MASKED || 8 * i + e < nvalid) ? q : 0u) << (4 * e);
+        }
+        w[i] = acc;
+    }
+
+    if (!live) return;
+    if (sub == 0) {
+        a.scale_f16[row] = scale_bits;
+        a.bias_f16[row] = bias_bits;
+    }
+    const int nbytes_row = (d + 1) / 2;
+    uint8_t* out = a.codes + row * nbytes_row + base / 2;
+    if (MASK != 2 && a.vec_stores >= 1) {  // dim % 8 == 0: rows are whole 4-byte words, 4-byte aligned
+        uint32_t* o = reinterpret_cast<uint32_t*>(out);
+#pragma unroll
+        for (int i = 0; i < NWORDS; ++i)
+            if (!MASKED || 8 * i < nvalid) o[i] = w[i];
+    } else {
+        const int nb = (nvalid + 1) / 2;  // bytes this lane owns
+#pragma unroll
+        for (int b = 0; b < E / 2; ++b)
+            if (b < nb) out[b] = (uint8_t)(w[b / 4] >> (8 * (b % 4)));
+    }
+}
+
+template <int E, int L, typename Tin, int MASK>
+inline hipError_t launch_greedy_swl(const GreedyArgs& a, int32_t d, hipStream_t stream)
+{
+    constexpr int kRowsPerBlock = kSwlBlock / L;
+    const int64_t blocks = (a.rows + kRowsPerBlock - 1) / kRowsPerBlock;
+    hipLaunchKernelGGL((greedy_swl_kernel<E, L, Tin, MASK>), dim3((unsigned)blocks), dim3(kSwlBlock), 0, stream, a, d);
+    return hipGetLastError();
+}
+
+// Dispatch over the (E, L) layouts that the including translation unit lists in E4Q_SWL_LAYOUTS.
+// Its body differs between translation units, so it has internal linkage.  The mask mode follows
+// from dim: none if dim == E*L, per block of 8 if dim % 8 == 0, else per element.
+namespace {
+template <typename Tin>
+hipError_t dispatch_greedy_swl(const GreedyArgs& a, int32_t d, int E, int L, hipStream_t stream)
+{
+    const int mask = (d == E * L) ? 0 : (d % 8 == 0 ? 1 : 2);
+#define E4Q_SWL(EE, LL)                                                              \
+    if (E == EE && L == LL) {                                                        \
+        if (mask == 0) return launch_greedy_swl<EE, LL, Tin, 0>(a, d, stream);       \
+        if (mask == 1) return launch_greedy_swl<EE, LL, Tin, 1>(a, d, stream);       \
+        return launch_greedy_swl<EE, LL, Tin, 2>(a, d, stream);                      \
+    }
+    E4Q_SWL_LAYOUTS
+#undef E4Q_SWL
+    return hipErrorInvalidValue;
+}
+}  // namespace
+
+}  // namespace e4q

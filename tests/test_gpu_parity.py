@@ -12,6 +12,8 @@ import numpy as np
 import pytest
 import torch
 
+from helpers import f16_bits
+
 pytestmark = pytest.mark.gpu
 
 L2_RTOL = 1e-5
@@ -100,31 +102,84 @@ def test_config4_batch_of_half_tables(e4q, oracle_lib):
 
 
 # --------------------------------------------------------------------------------------------
-# Every register-resident dimension, both input types, ragged row counts; and the LDS fallback
+# Every kernel layout.  The library picks by (rows, dim, ratio): one row per lane for many rows and
+# dim in 8, 16, ..., 128; otherwise L lanes per row with E elements per lane (E = 8 for few rows,
+# up to 128 for many rows), unmasked / masked per block of 8 / masked per element.
 # --------------------------------------------------------------------------------------------
+MANY = 64 * 512 + 17   # enough rows for the one-row-per-lane kernels (and a ragged tail)
+
+
 @pytest.mark.parametrize("dtype", [torch.float32, torch.float16])
 @pytest.mark.parametrize("dim", list(range(8, 129, 8)))
-def test_every_fast_dimension(e4q, oracle_lib, dim, dtype):
+def test_row_per_lane_every_dimension(e4q, oracle_lib, dim, dtype):
+    from helpers import oracle_rows_in_parallel
     from paper_1911_02079_amd import synth
 
-    t = synth.outlier_table(64 * 5 + 17, dim, seed=1000 + dim, device="cuda").to(dtype)
-    compare_with_oracle(e4q, oracle_lib, t, 200, 0.16, f"fast dim={dim}")
+    t = synth.outlier_table(MANY, dim, seed=1000 + dim, device="cuda").to(dtype)
+    say(f"row-per-lane dim={dim} {dtype} rows={MANY}")
+    codes, scale, bias = e4q.quantize_rowwise_greedy(t, 200, 0.16)
+    torch.cuda.synchronize()
+    o = oracle_rows_in_parallel(oracle_lib, t.cpu().numpy(), 200, 0.16)
+    assert np.array_equal(codes.cpu().numpy(), o[0])
+    assert np.array_equal(f16_bits(scale), o[1]) and np.array_equal(f16_bits(bias), o[2])
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.float16])
-@pytest.mark.parametrize("dim", [1, 2, 3, 5, 7, 12, 33, 63, 100, 130, 200, 256, 257, 1000])
-def test_fallback_dimensions(e4q, oracle_lib, dim, dtype):
+@pytest.mark.parametrize("dim", [1, 2, 3, 5, 7, 8, 12, 16, 24, 33, 40, 63, 64, 100, 128, 130, 200, 256, 257, 504, 512,
+                                 513, 1000, 1024, 2000, 2048, 3000])
+def test_few_rows_every_layout(e4q, oracle_lib, dim, dtype):
+    """Few rows: 8 elements per lane up to dim 512, then 16 / 32 / 64 per lane with 64 lanes per row."""
     from paper_1911_02079_amd import synth
 
     t = synth.outlier_table(131, dim, seed=2000 + dim, device="cuda").to(dtype)
-    compare_with_oracle(e4q, oracle_lib, t, 50, 0.3, f"fallback dim={dim}")
+    compare_with_oracle(e4q, oracle_lib, t, 50, 0.3, f"few rows dim={dim}")
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.float16])
+@pytest.mark.parametrize("dim", [4, 12, 20, 36, 50, 100, 127, 136, 192, 200, 256, 300, 512, 1000, 1024, 2048])
+def test_many_rows_long_chunks(e4q, oracle_lib, dim, dtype):
+    """Many rows and a dimension without a one-row-per-lane kernel: up to 128 elements per lane."""
+    from helpers import oracle_rows_in_parallel
+    from paper_1911_02079_amd import synth
+
+    rows = MANY if dim <= 512 else 64 * 512 + 3
+    t = synth.gaussian_table(rows, dim, 0.1, seed=3000 + dim, device="cuda").to(dtype)
+    say(f"long chunks dim={dim} {dtype} rows={rows}")
+    codes, scale, bias = e4q.quantize_rowwise_greedy(t, 20, 0.25)
+    torch.cuda.synchronize()
+    o = oracle_rows_in_parallel(oracle_lib, t.cpu().numpy(), 20, 0.25)
+    bad = np.flatnonzero((codes.cpu().numpy() != o[0]).any(axis=1) | (f16_bits(scale) != o[1]) | (f16_bits(bias) != o[2]))
+    assert bad.size == 0, f"{bad.size} rows differ, first {bad[:5]}"
 
 
 def test_largest_dimension(e4q, oracle_lib):
     from paper_1911_02079_amd import synth
 
     t = synth.gaussian_table(9, 4096, 0.1, seed=7, device="cuda")
-    compare_with_oracle(e4q, oracle_lib, t, 20, 0.25, "dim=4096")
+    compare_with_oracle(e4q, oracle_lib, t, 20, 0.25, "dim=4096 few rows")
+    t = synth.gaussian_table(64 * 512 + 1, 4096, 0.1, seed=8, device="cuda")
+    say("dim=4096 many rows")
+    codes, scale, bias = e4q.quantize_rowwise_greedy(t, 4, 0.5)
+    torch.cuda.synchronize()
+    from helpers import oracle_rows_in_parallel
+
+    o = oracle_rows_in_parallel(oracle_lib, t.cpu().numpy(), 4, 0.5)
+    assert np.array_equal(codes.cpu().numpy(), o[0]) and np.array_equal(f16_bits(scale), o[1])
+
+
+@pytest.mark.parametrize("dim", [8, 24, 64, 100, 128, 256, 1000])
+def test_ratio_zero_many_rows(e4q, oracle_lib, dim):
+    """Plain min/max quantization (ratio 0) always takes the 8-elements-per-lane layout."""
+    from helpers import oracle_rows_in_parallel
+    from paper_1911_02079_amd import synth
+
+    t = synth.outlier_table(50_001, dim, seed=4000 + dim, device="cuda")
+    say(f"ratio=0 dim={dim}")
+    codes, scale, bias = e4q.quantize_rowwise_greedy(t, 200, 0.0)
+    torch.cuda.synchronize()
+    o = oracle_rows_in_parallel(oracle_lib, t.cpu().numpy(), 200, 0.0)
+    assert np.array_equal(codes.cpu().numpy(), o[0])
+    assert np.array_equal(f16_bits(scale), o[1]) and np.array_equal(f16_bits(bias), o[2])
 
 
 # --------------------------------------------------------------------------------------------
@@ -221,8 +276,7 @@ def test_outputs_do_not_overrun(e4q):
     """Guard bands around the outputs stay untouched (ragged row count, fast and fallback paths)."""
     from paper_1911_02079_amd import synth
 
-    for dim in (64, 13):
-        rows = 64 * 3 + 5
+    for dim, rows in ((64, 64 * 3 + 5), (13, 64 * 3 + 5), (64, 64 * 512 + 5), (200, 64 * 512 + 5)):
         t = synth.gaussian_table(rows, dim, 0.1, seed=9, device="cuda")
         nb = (dim + 1) // 2
         say(f"guard bands dim={dim}")

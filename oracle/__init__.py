@@ -4,7 +4,7 @@ TEST INFRASTRUCTURE ONLY: the test-suite, the smoke check and the benchmark's
 CPU-baseline leg are the only callers.  The HIP library never imports this
 package and this package never imports the HIP binding.
 
-`oracle.build()` compiles `e4q_oracle.c` with gcc into `libe4q_oracle.so`
+`oracle.build()` compiles `e4q_oracle.c` and `e4q_oracle_kmeans.c` with gcc into `libe4q_oracle.so`
 next to it; the functions below are thin ctypes wrappers taking and returning
 NumPy arrays.  See the header of `e4q_oracle.c` for what is computed and which
 passages of the paper each step follows.
@@ -18,7 +18,7 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = os.path.join(_HERE, "e4q_oracle.c")
+_SRCS = [os.path.join(_HERE, "e4q_oracle.c"), os.path.join(_HERE, "e4q_oracle_kmeans.c")]
 _LIB_PATH = os.path.join(_HERE, "libe4q_oracle.so")
 _lib = None
 
@@ -29,9 +29,10 @@ _CFLAGS = ["-O2", "-ffp-contract=off", "-fno-fast-math", "-mfma", "-msse4.1", "-
 
 def build(force: bool = True) -> str:
     """Compile the C oracle.  Returns the path of the shared library."""
-    if force or not os.path.exists(_LIB_PATH) or os.path.getmtime(_LIB_PATH) < os.path.getmtime(_SRC):
+    if (force or not os.path.exists(_LIB_PATH)
+            or os.path.getmtime(_LIB_PATH) < max(os.path.getmtime(p) for p in _SRCS)):
         tmp = _LIB_PATH + f".tmp{os.getpid()}"
-        subprocess.run(["gcc", *_CFLAGS, "-o", tmp, _SRC, "-lm"], check=True)
+        subprocess.run(["gcc", *_CFLAGS, "-o", tmp, *_SRCS, "-lm"], check=True)
         os.replace(tmp, _LIB_PATH)
     return _LIB_PATH
 
@@ -62,6 +63,12 @@ def _load():
     lib.e4q_oracle_dequantize.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_int64, c.c_int32,
                                           c.c_void_p]
     lib.e4q_oracle_dequantize.restype = c.c_int
+    lib.e4q_oracle_quantize_rowwise_kmeans16.argtypes = [
+        c.c_void_p, c.c_int, c.c_int64, c.c_int32, c.c_int64, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p]
+    lib.e4q_oracle_quantize_rowwise_kmeans16.restype = c.c_int
+    lib.e4q_oracle_dequantize_codebook.argtypes = [c.c_void_p, c.c_void_p, c.c_int64, c.c_int32,
+                                                   c.c_void_p]
+    lib.e4q_oracle_dequantize_codebook.restype = c.c_int
     _lib = lib
     return lib
 
@@ -156,6 +163,35 @@ def dequantize(codes: np.ndarray, scale_f16: np.ndarray, bias_f16: np.ndarray, d
     assert codes.shape[1] == (dim + 1) // 2
     out = np.empty((rows, dim), dtype=np.float32)
     rc = _load().e4q_oracle_dequantize(_ptr(codes), _ptr(scale_f16), _ptr(bias_f16), rows, dim, _ptr(out))
+    if rc != 0:
+        raise ValueError("oracle rejected the arguments")
+    return out
+
+
+def quantize_rowwise_kmeans16(table: np.ndarray, lloyd_iters: int = 20, return_centres: bool = False):
+    """Row-wise 16-entry codebook (Section 3, "Codebook-based Quantization").  Returns
+    (idx uint8 [rows, ceil(dim/2)], centroids_f16 uint16 [rows, 16]) and, if `return_centres`,
+    also the float32 centres before binary16 rounding."""
+    t, dtype = _as_table(table)
+    rows, dim = t.shape
+    idx = np.zeros((rows, (dim + 1) // 2), dtype=np.uint8)
+    cent = np.zeros((rows, 16), dtype=np.uint16)
+    c32 = np.zeros((rows, 16), dtype=np.float32)
+    rc = _load().e4q_oracle_quantize_rowwise_kmeans16(_ptr(t), dtype, rows, dim, dim, int(lloyd_iters),
+                                                      _ptr(idx), _ptr(cent), _ptr(c32))
+    if rc != 0:
+        raise ValueError("oracle rejected the arguments")
+    return (idx, cent, c32) if return_centres else (idx, cent)
+
+
+def dequantize_codebook(idx: np.ndarray, centroids_f16: np.ndarray, dim: int) -> np.ndarray:
+    """out[r][k] = codebook[r][index[r][k]] widened to float32."""
+    idx = np.ascontiguousarray(idx, dtype=np.uint8)
+    centroids_f16 = np.ascontiguousarray(centroids_f16, dtype=np.uint16)
+    rows = idx.shape[0]
+    assert idx.shape[1] == (dim + 1) // 2 and centroids_f16.shape == (rows, 16)
+    out = np.empty((rows, dim), dtype=np.float32)
+    rc = _load().e4q_oracle_dequantize_codebook(_ptr(idx), _ptr(centroids_f16), rows, dim, _ptr(out))
     if rc != 0:
         raise ValueError("oracle rejected the arguments")
     return out

@@ -14,6 +14,21 @@ import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
+KMEANS_MUTANTS = {
+    "sixteen_grid_intervals": ("float step = (hi - lo) / 15.0f;", "float step = (hi - lo) / 16.0f;"),
+    "ties_take_the_higher_index": ("if (dk < bd) { bd = dk; best = k; }", "if (dk <= bd) { bd = dk; best = k; }"),
+    "one_round_short": ("for (int it = 0; it < lloyd_iters; ++it) {", "for (int it = 1; it < lloyd_iters; ++it) {"),
+    "empty_cluster_moves_to_zero": ("if (cnt[k] > 0) c[k] = (float)(sum[k] / (double)cnt[k]);",
+                                    "c[k] = cnt[k] > 0 ? (float)(sum[k] / (double)cnt[k]) : 0.0f;"),
+    "sum_instead_of_mean": ("c[k] = (float)(sum[k] / (double)cnt[k]);", "c[k] = (float)(sum[k]);"),
+    "indices_from_unrounded_centres": ("unsigned q0 = (unsigned)nearest_centre(x[2 * b], ch);",
+                                       "unsigned q0 = (unsigned)nearest_centre(x[2 * b], c);"),
+    "index_nibbles_swapped": ("out[b] = (uint8_t)(q0 | (q1 << 4));\n            }\n        } else {",
+                              "out[b] = (uint8_t)(q1 | (q0 << 4));\n            }\n        } else {"),
+    "small_rows_clustered": ("if (dim <= K) {", "if (dim <= 0) {"),
+    "squared_distance_sign": ("float dk = fabsf(x - c[k]);", "float dk = x - c[k];"),
+}
+
 MUTANTS = {
     "sixteen_levels": ("#define E4Q_QMAX 15.0f", "#define E4Q_QMAX 16.0f"),
     "tie_moves_lower_bound": ("if (loss_l < loss_r) {", "if (loss_l <= loss_r) {"),
@@ -40,12 +55,12 @@ MUTANTS = {
 }
 
 
-def _run_pins(oracle_parent):
+def _run_pins(oracle_parent, test_file="test_oracle_pins.py"):
     env = dict(os.environ)
     if oracle_parent:
         env["E4Q_TEST_ORACLE_PARENT"] = oracle_parent
     return subprocess.run(
-        [sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", "test_oracle_pins.py"), "-x", "-q",
+        [sys.executable, "-m", "pytest", os.path.join(ROOT, "tests", test_file), "-x", "-q",
          "-k", "not numpy_twin", "-p", "no:cacheprovider"],
         cwd=ROOT, env=env, capture_output=True, text=True, timeout=600)
 
@@ -55,7 +70,7 @@ def test_pins_catch_planted_mistake(name, tmp_path):
     old, new = MUTANTS[name]
     dst = tmp_path / "oracle"
     dst.mkdir()
-    for f in ("__init__.py", "numpy_twin.py", "e4q_oracle.c"):
+    for f in ("__init__.py", "numpy_twin.py", "e4q_oracle.c", "e4q_oracle_kmeans.c"):
         shutil.copy(os.path.join(ROOT, "oracle", f), dst / f)
     src = (dst / "e4q_oracle.c").read_text()
     assert src.count(old) >= 1, f"mutation site for {name} no longer exists in the oracle"
@@ -63,3 +78,17 @@ def test_pins_catch_planted_mistake(name, tmp_path):
     res = _run_pins(str(tmp_path))
     assert res.returncode != 0, f"pins did not notice mutant '{name}':\n{res.stdout[-2000:]}"
     assert "failed" in res.stdout or "error" in res.stdout.lower()
+
+
+@pytest.mark.parametrize("name", sorted(KMEANS_MUTANTS))
+def test_kmeans_pins_catch_planted_mistake(name, tmp_path):
+    old, new = KMEANS_MUTANTS[name]
+    dst = tmp_path / "oracle"
+    dst.mkdir()
+    for f in ("__init__.py", "numpy_twin.py", "e4q_oracle.c", "e4q_oracle_kmeans.c"):
+        shutil.copy(os.path.join(ROOT, "oracle", f), dst / f)
+    src = (dst / "e4q_oracle_kmeans.c").read_text()
+    assert src.count(old) >= 1, f"mutation site for {name} no longer exists in the oracle"
+    (dst / "e4q_oracle_kmeans.c").write_text(src.replace(old, new, 1))
+    res = _run_pins(str(tmp_path), "test_oracle_kmeans_pins.py")
+    assert res.returncode != 0, f"pins did not notice mutant '{name}':\n{res.stdout[-2000:]}"

@@ -1,16 +1,18 @@
 #!/usr/bin/env python3
-"""Benchmark of the hot path on one MI355X: row-wise greedy 4-bit quantization of a seeded
-synthetic embedding table (then de-quantization of the result), through libe4q's C ABI.
+"""Benchmark of the hot path on one MI355X, through libe4q's C ABI.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload laplace_10M_x_128]
 
-One "step" is one pass of the whole path over the table, which is already resident in HBM:
-`quantize_rowwise_greedy` (row load, min/max, Algorithm 1's search, encode + pack, binary16
-scale/bias) followed by `dequantize` of its output.  Prints ONE JSON line.  `value` is rows per
-second over whole steps; the `kernels` object gives each kernel's own average duration from HIP
-events recorded on the launch stream inside the timed region; `roofline` prices the dominant
-kernel (the greedy search, bound by plain fp32 VALU issue); `cpu_baseline` is the CPU oracle
-timed on this machine's host cores on a bounded sample of the same table.
+Default workload (the one the headline metric is quoted on): row-wise greedy 4-bit quantization
+of a seeded synthetic 10 M x 128 fp32 table, then de-quantization of the result.  One "step" is
+one pass of the whole path over the table, which is already resident in HBM: the quantizer (row
+load, min/max, Algorithm 1's search, encode + pack, binary16 scale/bias) followed by the
+de-quantizer.  `--workload mixture_2M_x_64_kmeans16` times the codebook variant the same way.
+
+Prints ONE JSON line.  `value` is rows per second over whole steps; `kernels` gives each kernel's
+own average duration from HIP events recorded on the launch stream inside the timed region;
+`roofline` prices the dominant kernel (bound by plain fp32 VALU issue); `cpu_baseline` is the CPU
+oracle timed on this machine's host cores on a bounded sample of the same table.
 """
 from __future__ import annotations
 
@@ -33,14 +35,15 @@ PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
 PEAK_HBM_BYTES = 8.0e12
 
 WORKLOADS = {
-    # name: (generator, rows, dim, n_bins, ratio)
-    "gaussian_10k_x_64": ("gaussian_table", 10_000, 64, 200, 0.16),
-    "outlier_1M_x_64": ("outlier_table", 1_000_000, 64, 200, 0.16),
-    "laplace_10M_x_128": ("laplace_offset_table", 10_000_000, 128, 200, 0.16),
+    # name: (method, generator, rows, dim, parameters)
+    "gaussian_10k_x_64": ("greedy", "gaussian_table", 10_000, 64, {"n_bins": 200, "ratio": 0.16}),
+    "outlier_1M_x_64": ("greedy", "outlier_table", 1_000_000, 64, {"n_bins": 200, "ratio": 0.16}),
+    "laplace_10M_x_128": ("greedy", "laplace_offset_table", 10_000_000, 128, {"n_bins": 200, "ratio": 0.16}),
+    "mixture_2M_x_64_kmeans16": ("kmeans16", "mixture_table", 2_000_000, 64, {"lloyd_iters": 20}),
 }
 
 
-def algorithmic_lane_ops_per_row(dim: int, n_iter: int) -> int:
+def greedy_lane_ops_per_row(dim: int, n_iter: int) -> int:
     """fp32 lane operations the method itself needs per row: 8 per element per scored range
     (subtract, multiply, round, clamp, fused multiply-add, subtract, multiply, add) for the
     1 + 2*n_iter ranges of Algorithm 1, 2 per element for min/max, 6 per element for the final
@@ -48,9 +51,12 @@ def algorithmic_lane_ops_per_row(dim: int, n_iter: int) -> int:
     return (1 + 2 * n_iter) * dim * 8 + 2 * dim + 6 * dim
 
 
-def algorithmic_bytes_per_row(dim: int, elem_bytes: int = 4) -> int:
-    """Row read once, packed codes + binary16 scale and bias written once."""
-    return dim * elem_bytes + (dim + 1) // 2 + 4
+def kmeans_lane_ops_per_row(dim: int, iters: int) -> int:
+    """Lane operations of the 16-means path per row: per element and Lloyd round 16 subtractions,
+    15 compares, 15 minimum updates, 15 index selects and one binary64 add (62); one more
+    assignment pass against the rounded codebook (61 per element); 16 means per round (counted as
+    one operation each); 2 per element for min/max."""
+    return dim * (62 * iters + 61) + 16 * iters + 2 * dim
 
 
 def read_traffic(name: str):
@@ -64,26 +70,23 @@ def read_traffic(name: str):
         return None
 
 
-def cpu_baseline(table_gpu, n_bins: int, ratio: float, target_seconds: float = 15.0):
+def cpu_baseline(table_gpu, run_oracle, target_seconds: float = 12.0):
     """Times the CPU oracle (as it stands) on a prefix of the same table, rows partitioned over
     the host cores available to this process (16 at most)."""
     import numpy as np
-
-    import oracle
 
     cores = max(1, min(16, len(os.sched_getaffinity(0))))
     rows = table_gpu.shape[0]
     probe = np.ascontiguousarray(table_gpu[: min(rows, 2048)].cpu().numpy())
     t0 = time.perf_counter()
-    oracle.quantize_rowwise_greedy(probe, n_bins, ratio)
+    run_oracle(probe)
     per_row = (time.perf_counter() - t0) / probe.shape[0]
     sample_rows = int(min(rows, 4_000_000, max(cores * 64, target_seconds * cores / per_row)))
     sample = np.ascontiguousarray(table_gpu[:sample_rows].cpu().numpy())
     bounds = [sample_rows * k // cores for k in range(cores + 1)]
     t0 = time.perf_counter()
     with ThreadPoolExecutor(max_workers=cores) as pool:  # ctypes releases the GIL inside the C call
-        list(pool.map(lambda k: oracle.quantize_rowwise_greedy(sample[bounds[k]:bounds[k + 1]], n_bins, ratio),
-                      range(cores)))
+        list(pool.map(lambda k: run_oracle(sample[bounds[k]:bounds[k + 1]]), range(cores)))
     dt = time.perf_counter() - t0
     return {"value": sample_rows / dt, "unit": "rows/s", "cores": cores, "kind": "oracle",
             "sample": f"first {sample_rows} rows of the same table, rows split over {cores} threads, "
@@ -116,21 +119,51 @@ def main() -> int:
         return 2
     e4q.binding.load_library()
     torch.cuda.set_device(0)
-    gen, rows, dim, n_bins, ratio = WORKLOADS[args.workload]
-    n_iter = e4q.greedy_iterations(n_bins, ratio)
+    method, gen, rows, dim, params = WORKLOADS[args.workload]
 
     table = getattr(synth, gen)(rows, dim, device="cuda:0")
-    out = e4q.alloc_outputs(rows, dim, table.device)
     xh = torch.empty((rows, dim), dtype=torch.float32, device=table.device)
+    if method == "greedy":
+        n_bins, ratio = params["n_bins"], params["ratio"]
+        n_iter = e4q.greedy_iterations(n_bins, ratio)
+        out = e4q.alloc_outputs(rows, dim, table.device)
+        quantize = lambda: e4q.quantize_rowwise_greedy(table, n_bins, ratio, out=out)  # noqa: E731
+        dequantize = lambda: e4q.dequantize(out[0], out[1], out[2], dim, out=xh)  # noqa: E731
+        q_name, dq_name = "greedy_rpl_kernel", "dequantize_w4_kernel"
+        ops_per_row = greedy_lane_ops_per_row(dim, n_iter)
+        out_bytes_per_row = (dim + 1) // 2 + 4
+        config = {"n_bins": n_bins, "ratio": ratio, "candidate_ranges_per_row": 1 + 2 * n_iter, "nbits": 4,
+                  "step": "quantize_rowwise_greedy + dequantize, table resident in HBM"}
+        metric = "rows quantized/sec (greedy 4-bit)"
+
+        def run_oracle(t):
+            import oracle
+            return oracle.quantize_rowwise_greedy(t, n_bins, ratio)
+    else:
+        iters = params["lloyd_iters"]
+        out = (torch.empty((rows, (dim + 1) // 2), dtype=torch.uint8, device=table.device),
+               torch.empty((rows, 16), dtype=torch.float16, device=table.device))
+        quantize = lambda: e4q.quantize_rowwise_kmeans16(table, iters, out=out)  # noqa: E731
+        dequantize = lambda: e4q.dequantize_codebook(out[0], out[1], dim, out=xh)  # noqa: E731
+        q_name, dq_name = "kmeans16_rpl_kernel", "dequantize_codebook_w4_kernel"
+        ops_per_row = kmeans_lane_ops_per_row(dim, iters)
+        out_bytes_per_row = (dim + 1) // 2 + 32
+        config = {"lloyd_iters": iters, "codebook_entries": 16, "nbits": 4,
+                  "step": "quantize_rowwise_kmeans16 + dequantize_codebook, table resident in HBM"}
+        metric = "rows quantized/sec (16-means codebook, 4-bit)"
+
+        def run_oracle(t):
+            import oracle
+            return oracle.quantize_rowwise_kmeans16(t, iters)
     torch.cuda.synchronize()
 
     def step(events=None):
         if events is not None:
             events[0].record()
-        e4q.quantize_rowwise_greedy(table, n_bins, ratio, out=out)
+        quantize()
         if events is not None:
             events[1].record()
-        e4q.dequantize(out[0], out[1], out[2], dim, out=xh)
+        dequantize()
         if events is not None:
             events[2].record()
 
@@ -150,53 +183,48 @@ def main() -> int:
         src = torch.ones(1 << 28, dtype=torch.float32, device=table.device)  # 1 GiB
         dst = torch.empty_like(src)
         for _ in range(3):
-            dst.copy_(src)  # one elementwise copy kernel: reads 1 GiB, writes 1 GiB
+            dst.copy_(src)  # one plain copy kernel: reads 1 GiB, writes 1 GiB
         torch.cuda.synchronize()
         del src, dst
 
-    ms_per_step = 1e3 * elapsed / args.steps
-    greedy_ms = sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps
-    dequant_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps
-
-    lane_ops = algorithmic_lane_ops_per_row(dim, n_iter) * rows
-    q_bytes = algorithmic_bytes_per_row(dim) * rows
-    dq_bytes = ((dim + 1) // 2 + 4 + 4 * dim) * rows
-    achieved = lane_ops / (greedy_ms * 1e-3)
+    q_ms = sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps
+    dq_ms = sum(e[1].elapsed_time(e[2]) for e in evs) / args.steps
+    q_bytes = (dim * table.element_size() + out_bytes_per_row) * rows
+    dq_bytes = (out_bytes_per_row + 4 * dim) * rows
+    achieved = ops_per_row * rows / (q_ms * 1e-3)
     result = {
-        "metric": "rows quantized/sec (greedy 4-bit)",
+        "metric": metric,
         "value": rows / (elapsed / args.steps),
         "unit": "rows/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": ms_per_step,
+        "ms_per_step": 1e3 * elapsed / args.steps,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": args.workload, "rows": rows, "dim": dim, "n_bins": n_bins, "ratio": ratio,
-                   "candidate_ranges_per_row": 1 + 2 * n_iter, "nbits": 4,
-                   "step": "quantize_rowwise_greedy + dequantize, table resident in HBM"},
+        "config": dict({"workload": args.workload, "rows": rows, "dim": dim}, **config),
         "kernels": {
-            "greedy_rpl_kernel": {"avg_ms": greedy_ms, "rows_per_s": rows / (greedy_ms * 1e-3),
-                                  "algorithmic_GBps": q_bytes / (greedy_ms * 1e-3) / 1e9},
-            "dequantize_w4_kernel": {"avg_ms": dequant_ms, "algorithmic_GBps": dq_bytes / (dequant_ms * 1e-3) / 1e9,
-                                     "frac_of_hbm_peak": dq_bytes / (dequant_ms * 1e-3) / PEAK_HBM_BYTES},
+            q_name: {"avg_ms": q_ms, "rows_per_s": rows / (q_ms * 1e-3),
+                     "algorithmic_GBps": q_bytes / (q_ms * 1e-3) / 1e9},
+            dq_name: {"avg_ms": dq_ms, "algorithmic_GBps": dq_bytes / (dq_ms * 1e-3) / 1e9,
+                      "frac_of_hbm_peak": dq_bytes / (dq_ms * 1e-3) / PEAK_HBM_BYTES},
         },
         "roofline": {
-            "kernel": "greedy_rpl_kernel", "bound": "alu", "achieved": achieved / 1e12,
+            "kernel": q_name, "bound": "alu", "achieved": achieved / 1e12,
             "peak": PEAK_LANE_OPS / 1e12, "unit": "T lane-op/s (plain fp32 VALU: 256 CU x 64 lanes x 2.4 GHz)",
             "frac": achieved / PEAK_LANE_OPS,
-            "lane_ops_per_row": algorithmic_lane_ops_per_row(dim, n_iter),
-            "bytes_per_row": algorithmic_bytes_per_row(dim),
-            "hbm_achieved_GBps": q_bytes / (greedy_ms * 1e-3) / 1e9,
-            "hbm_frac": q_bytes / (greedy_ms * 1e-3) / PEAK_HBM_BYTES,
-            "traffic": read_traffic(f"greedy_rpl_kernel_{args.workload}_hbm_traffic.txt"),
+            "lane_ops_per_row": ops_per_row,
+            "bytes_per_row": q_bytes // rows,
+            "hbm_achieved_GBps": q_bytes / (q_ms * 1e-3) / 1e9,
+            "hbm_frac": q_bytes / (q_ms * 1e-3) / PEAK_HBM_BYTES,
+            "traffic": read_traffic(f"{q_name}_{args.workload}_hbm_traffic.txt"),
         },
     }
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(table, n_bins, ratio)
+        result["cpu_baseline"] = cpu_baseline(table, run_oracle)
     print(json.dumps(result), flush=True)
     return 0
 

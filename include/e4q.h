@@ -116,6 +116,35 @@ int e4q_quantize_rowwise_greedy_batch(const e4q_table_desc* descs, int32_t n_tab
                                       void* hip_stream);
 
 /*
+ * Row-wise codebook quantization ("KMEANS": Section 3, "Codebook-based Quantization"; initial
+ * centres and binary16 codebooks as in Section 4).  For each row independently, 1-D k-means with
+ * 16 centres: centres start on the uniform grid min + k*(max-min)/15; `lloyd_iters` rounds of
+ * (assign every value to its nearest centre -- |x - c| in binary32, the lowest index among equal
+ * distances --, move every non-empty cluster's centre to the mean of its members -- summed in
+ * binary64 in element order, one division, rounded to binary32); no convergence test.  The
+ * centres are then rounded to binary16 and each value is stored as the 4-bit index of its nearest
+ * ROUNDED centre.  Rows with dim <= 16 are not clustered: codebook entry k is element k rounded
+ * to binary16 (unused entries +0) and index k is k.
+ *
+ *   table, dtype, rows, dim, row_stride   as for e4q_quantize_rowwise_greedy
+ *   lloyd_iters          >= 0 (the benchmark configuration uses 20)
+ *   idx            [out] rows x ceil(dim/2) bytes, two indices per byte, low nibble first
+ *   centroids_f16  [out] rows x 16 binary16 values (32 bytes per row, dense)
+ * Bytes per row: dim/2 + 32 (the KMEANS (FP16) sizes of Table 3).
+ */
+int e4q_quantize_rowwise_kmeans16(const void* table, int dtype, int64_t rows, int32_t dim,
+                                  int64_t row_stride, int32_t lloyd_iters, uint8_t* idx,
+                                  uint16_t* centroids_f16, void* hip_stream);
+
+/*
+ * Codebook de-quantization: out[r][k] = codebook[r][index[r][k]] widened to binary32
+ * (Section 3: each value is represented by the codebook entry its index names).
+ *   out  [out] rows x dim binary32, dense
+ */
+int e4q_dequantize_codebook(const uint8_t* idx, const uint16_t* centroids_f16, int64_t rows, int32_t dim,
+                            float* out, void* hip_stream);
+
+/*
  * n_iter = ceil(n_bins * ratio) clamped to [0, n_bins - 1]: the number of trips of the loop of
  * Algorithm 1 in exact arithmetic (each trip scores two candidate ranges).  `ratio` is a
  * binary32 number and may sit a relative 2^-24 off the decimal the caller wrote, so the product

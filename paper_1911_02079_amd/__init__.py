@@ -8,7 +8,7 @@ the built library) and seeded synthetic-table generators (`synth.py`).
 from . import synth  # noqa: F401
 
 __all__ = ["synth", "binding", "quantize_rowwise_greedy", "quantize_rowwise_greedy_batch", "dequantize",
-           "greedy_iterations"]
+           "greedy_iterations", "quantize_rowwise_kmeans16", "dequantize_codebook"]
 
 
 def __getattr__(name):
@@ -17,7 +17,7 @@ def __getattr__(name):
 
         return importlib.import_module(".binding", __name__)
     if name in ("quantize_rowwise_greedy", "quantize_rowwise_greedy_batch", "dequantize", "greedy_iterations",
-                "alloc_outputs", "load_library", "E4QError"):
+                "alloc_outputs", "load_library", "E4QError", "quantize_rowwise_kmeans16", "dequantize_codebook"):
         import importlib
 
         return getattr(importlib.import_module(".binding", __name__), name)

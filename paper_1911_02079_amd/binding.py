@@ -54,6 +54,11 @@ def load_library() -> ctypes.CDLL:
     lib.e4q_dequantize.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_int64, c.c_int32, c.c_int32,
                                    c.c_void_p, c.c_void_p]
     lib.e4q_dequantize.restype = c.c_int
+    lib.e4q_quantize_rowwise_kmeans16.argtypes = [c.c_void_p, c.c_int, c.c_int64, c.c_int32, c.c_int64, c.c_int32,
+                                                  c.c_void_p, c.c_void_p, c.c_void_p]
+    lib.e4q_quantize_rowwise_kmeans16.restype = c.c_int
+    lib.e4q_dequantize_codebook.argtypes = [c.c_void_p, c.c_void_p, c.c_int64, c.c_int32, c.c_void_p, c.c_void_p]
+    lib.e4q_dequantize_codebook.restype = c.c_int
     lib.e4q_greedy_iterations.argtypes = [c.c_int32, c.c_float]
     lib.e4q_greedy_iterations.restype = c.c_int32
     lib.e4q_strerror.argtypes = [c.c_int]
@@ -179,5 +184,48 @@ def dequantize(codes: torch.Tensor, scale_f16: torch.Tensor, bias_f16: torch.Ten
     with torch.cuda.device(codes.device):
         rc = lib.e4q_dequantize(codes.data_ptr(), scale_f16.data_ptr(), bias_f16.data_ptr(), rows, int(dim),
                                 int(nbits), out.data_ptr(), _stream_ptr(stream, codes.device))
+    _check(rc)
+    return out
+
+
+def quantize_rowwise_kmeans16(table: torch.Tensor, lloyd_iters: int = 20,
+                              out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None,
+                              stream: Optional[torch.cuda.Stream] = None):
+    """e4q_quantize_rowwise_kmeans16.  Returns (idx uint8 [rows, ceil(dim/2)], centroids float16 [rows, 16])."""
+    lib = load_library()
+    _check_table(table)
+    rows, dim = table.shape
+    if out is None:
+        out = (torch.empty((rows, (dim + 1) // 2), dtype=torch.uint8, device=table.device),
+               torch.empty((rows, 16), dtype=torch.float16, device=table.device))
+    idx, cent = out
+    with torch.cuda.device(table.device):
+        rc = lib.e4q_quantize_rowwise_kmeans16(table.data_ptr(), _dtype_code(table), rows, dim,
+                                               table.stride(0) if rows > 1 else max(dim, table.stride(0)),
+                                               int(lloyd_iters), idx.data_ptr(), cent.data_ptr(),
+                                               _stream_ptr(stream, table.device))
+    _check(rc)
+    return idx, cent
+
+
+def dequantize_codebook(idx: torch.Tensor, centroids_f16: torch.Tensor, dim: int,
+                        out: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """e4q_dequantize_codebook: float32 [rows, dim] from packed indices and the float16 codebooks."""
+    lib = load_library()
+    if not (idx.is_cuda and centroids_f16.is_cuda):
+        raise ValueError("libe4q works on device memory only")
+    if idx.dtype != torch.uint8 or centroids_f16.dtype != torch.float16:
+        raise TypeError("idx must be uint8 and centroids float16")
+    rows = idx.shape[0]
+    if not (idx.is_contiguous() and centroids_f16.is_contiguous()) or idx.shape[1] != (dim + 1) // 2 \
+            or tuple(centroids_f16.shape) != (rows, 16):
+        raise ValueError("idx must be dense [rows, ceil(dim/2)] and centroids dense [rows, 16]")
+    if out is None:
+        out = torch.empty((rows, dim), dtype=torch.float32, device=idx.device)
+    elif out.dtype != torch.float32 or not out.is_contiguous() or tuple(out.shape) != (rows, dim):
+        raise ValueError("out must be a dense float32 [rows, dim] tensor")
+    with torch.cuda.device(idx.device):
+        rc = lib.e4q_dequantize_codebook(idx.data_ptr(), centroids_f16.data_ptr(), rows, int(dim), out.data_ptr(),
+                                         _stream_ptr(stream, idx.device))
     _check(rc)
     return out

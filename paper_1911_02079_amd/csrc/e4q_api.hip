@@ -150,6 +150,43 @@ int e4q_dequantize(const uint8_t* codes, const uint16_t* scale_f16, const uint16
     return err == hipSuccess ? E4Q_OK : fail_launch(err);
 }
 
+int e4q_quantize_rowwise_kmeans16(const void* table, int dtype, int64_t rows, int32_t dim,
+                                  int64_t row_stride, int32_t lloyd_iters, uint8_t* idx,
+                                  uint16_t* centroids_f16, void* hip_stream)
+{
+    if (lloyd_iters < 0) return E4Q_ERR_BAD_SEARCH;
+    if (dtype != E4Q_F32 && dtype != E4Q_F16) return E4Q_ERR_BAD_DTYPE;
+    if (rows < 0 || dim <= 0 || dim > E4Q_MAX_DIM || row_stride < dim) return E4Q_ERR_BAD_SHAPE;
+    if (rows == 0) return E4Q_OK;
+    if ((rows + 63) / 64 > 0x7fffffffLL) return E4Q_ERR_BAD_SHAPE;
+    if (!table || !idx || !centroids_f16) return E4Q_ERR_NULL_POINTER;
+    const size_t esz = dtype == E4Q_F32 ? 4 : 2;
+    if (!aligned(table, esz) || !aligned(centroids_f16, 2)) return E4Q_ERR_BAD_ALIGNMENT;
+    e4q::KMeansArgs a;
+    a.table = table;
+    a.rows = rows;
+    a.row_stride = row_stride;
+    a.lloyd_iters = lloyd_iters;
+    a.idx = idx;
+    a.centroids_f16 = centroids_f16;
+    a.vec_loads = (aligned(table, 16) && (row_stride * esz) % 16 == 0) ? 1u : 0u;
+    a.vec_stores = aligned(idx, 4) ? 1u : 0u;
+    const hipError_t err = e4q::launch_kmeans16(a, dtype, dim, static_cast<hipStream_t>(hip_stream));
+    return err == hipSuccess ? E4Q_OK : fail_launch(err);
+}
+
+int e4q_dequantize_codebook(const uint8_t* idx, const uint16_t* centroids_f16, int64_t rows, int32_t dim,
+                            float* out, void* hip_stream)
+{
+    if (rows < 0 || dim <= 0 || dim > E4Q_MAX_DIM) return E4Q_ERR_BAD_SHAPE;
+    if (rows == 0) return E4Q_OK;
+    if (!idx || !centroids_f16 || !out) return E4Q_ERR_NULL_POINTER;
+    if (!aligned(centroids_f16, 2) || !aligned(out, 4)) return E4Q_ERR_BAD_ALIGNMENT;
+    const hipError_t err = e4q::launch_dequantize_codebook(idx, centroids_f16, rows, dim, out,
+                                                           static_cast<hipStream_t>(hip_stream));
+    return err == hipSuccess ? E4Q_OK : fail_launch(err);
+}
+
 const char* e4q_strerror(int code)
 {
     switch (code) {

@@ -32,6 +32,21 @@ hipError_t launch_greedy_swl_f32_small(const GreedyArgs& a, int32_t dim, int E, 
 hipError_t launch_greedy_swl_f32_big(const GreedyArgs& a, int32_t dim, int E, int L, hipStream_t stream);
 hipError_t launch_greedy_swl_f16_small(const GreedyArgs& a, int32_t dim, int E, int L, hipStream_t stream);
 hipError_t launch_greedy_swl_f16_big(const GreedyArgs& a, int32_t dim, int E, int L, hipStream_t stream);
+
+// Arguments of the codebook (16-means) kernels.
+struct KMeansArgs {
+    const void* table;
+    int64_t rows;
+    int64_t row_stride;  // elements between rows
+    int32_t lloyd_iters;
+    uint8_t* idx;
+    uint16_t* centroids_f16;
+    uint32_t vec_loads;   // 1: table base and row pitch are 16-byte aligned
+    uint32_t vec_stores;  // >= 1: idx base is 4-byte aligned
+};
+hipError_t launch_kmeans16(const KMeansArgs& a, int dtype, int32_t dim, hipStream_t stream);
+hipError_t launch_dequantize_codebook(const uint8_t* idx, const uint16_t* centroids_f16, int64_t rows,
+                                      int32_t dim, float* out, hipStream_t stream);
 hipError_t launch_dequantize(const uint8_t* codes, const uint16_t* scale_f16, const uint16_t* bias_f16,
                              int64_t rows, int32_t dim, float* out, hipStream_t stream);
 

@@ -1,0 +1,169 @@
+// Row-wise 16-value codebook by 1-D k-means (Section 3, "Codebook-based Quantization"; Section 4:
+// centres start on ASYM's uniform grid, codebooks are stored in binary16).
+//
+// One table row per lane, the row in registers (dimension a compile-time constant), the 16 centres
+// in registers.  Per Lloyd round each element scans the 16 centres for the first nearest one
+// (binary32 distances, strict '<', so equal distances keep the lower index) and adds its value to
+// that cluster's binary64 sum; the sums and counts live in a lane-private column of LDS because
+// the cluster index is only known at run time (a register array cannot be indexed by it).  LDS
+// operations of a wave execute in order, so a cluster's sum is accumulated in element order, which
+// is what makes the result reproducible bit for bit.  Means are one binary64 division per
+// non-empty cluster and round; empty clusters keep their centre.  After the fixed number of rounds
+// the centres are rounded to binary16 and every element is assigned once more against the rounded
+// codebook, so the stored indices and the stored codebook agree.
+//
+// Arithmetic per element and round: 16 subtractions, 15 compares, 30 selects, one conversion and
+// one binary64 add: about 63 VALU operations; the path is bound by VALU issue like the greedy
+// search.  Rows with dim <= 16 need no clustering (every value is its own codebook entry).
+#pragma once
+
+#include "greedy_rpl.h"  // load_row
+#include "e4q_launch.h"
+
+namespace e4q {
+
+constexpr int kK = 16;
+
+// First index of the smallest |x - c[k]|.
+__device__ __forceinline__ int nearest_centre(float x, const float (&c)[kK])
+{
+    float best = __builtin_fabsf(x - c[0]);
+    int idx = 0;
+#pragma unroll
+    for (int k = 1; k < kK; ++k) {
+        const float dk = __builtin_fabsf(x - c[k]);
+        const bool lt = dk < best;
+        best = lt ? dk : best;
+        idx = lt ? k : idx;
+    }
+    return idx;
+}
+
+__device__ __forceinline__ void grid_centres(float lo, float hi, float (&c)[kK])
+{
+    const float step = (hi - lo) / kQMax;
+#pragma unroll
+    for (int k = 0; k < kK; ++k) c[k] = __builtin_fmaf((float)k, step, lo);
+}
+
+// Lane-private accumulators: entry k of lane l sits at [k * 64 + l].
+struct LloydScratch {
+    double sum[kK * 64];
+    uint32_t cnt[kK * 64];
+};
+
+__device__ __forceinline__ void lloyd_clear(LloydScratch& s, int lane)
+{
+#pragma unroll
+    for (int k = 0; k < kK; ++k) {
+        s.sum[k * 64 + lane] = 0.0;
+        s.cnt[k * 64 + lane] = 0u;
+    }
+}
+
+__device__ __forceinline__ void lloyd_add(LloydScratch& s, int lane, int a, float x)
+{
+    s.sum[a * 64 + lane] += (double)x;
+    s.cnt[a * 64 + lane] += 1u;
+}
+
+__device__ __forceinline__ void lloyd_update(const LloydScratch& s, int lane, float (&c)[kK])
+{
+#pragma unroll
+    for (int k = 0; k < kK; ++k) {
+        const uint32_t n = s.cnt[k * 64 + lane];
+        const float mean = (float)(s.sum[k * 64 + lane] / (double)n);
+        c[k] = n > 0u ? mean : c[k];
+    }
+}
+
+// Writes the 16 centres of one row as binary16 (32 bytes).
+__device__ __forceinline__ void store_codebook(const float (&c)[kK], uint16_t* __restrict__ cb)
+{
+    if (reinterpret_cast<uintptr_t>(cb) % 16 == 0) {
+        uint32_t w[kK / 2];
+#pragma unroll
+        for (int k = 0; k < kK / 2; ++k)
+            w[k] = (uint32_t)f16_bits(c[2 * k]) | ((uint32_t)f16_bits(c[2 * k + 1]) << 16);
+        uint4* o = reinterpret_cast<uint4*>(cb);
+        o[0] = make_uint4(w[0], w[1], w[2], w[3]);
+        o[1] = make_uint4(w[4], w[5], w[6], w[7]);
+    } else {
+#pragma unroll
+        for (int k = 0; k < kK; ++k) cb[k] = f16_bits(c[k]);
+    }
+}
+
+template <int D, typename Tin>
+__global__ void __launch_bounds__(64) kmeans16_rpl_kernel(KMeansArgs a)
+{
+    static_assert(D > kK, "rows with dim <= 16 take the other kernel");
+    __shared__ LloydScratch scratch;
+    const int lane = threadIdx.x;
+    const int64_t row = (int64_t)blockIdx.x * 64 + lane;
+    const bool live = row < a.rows;
+    const int64_t r = live ? row : a.rows - 1;
+
+    float x[D];
+    load_row<D>(static_cast<const Tin*>(a.table) + r * a.row_stride, a.vec_loads != 0, x);
+    float lo = x[0], hi = x[0];
+#pragma unroll
+    for (int k = 1; k < D; ++k) {
+        lo = __builtin_fminf(lo, x[k]);
+        hi = __builtin_fmaxf(hi, x[k]);
+    }
+    float c[kK];
+    grid_centres(lo, hi, c);
+
+    for (int it = 0; it < a.lloyd_iters; ++it) {
+        lloyd_clear(scratch, lane);
+#pragma unroll
+        for (int e = 0; e < D; ++e) lloyd_add(scratch, lane, nearest_centre(x[e], c), x[e]);
+        lloyd_update(scratch, lane, c);
+    }
+
+    float ch[kK];
+    constexpr int NWORDS = (D / 2 + 3) / 4;
+    uint32_t w[NWORDS];
+#pragma unroll
+    for (int k = 0; k < kK; ++k) ch[k] = through_f16(c[k]);
+#pragma unroll
+    for (int i = 0; i < NWORDS; ++i) {
+        uint32_t acc = 0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            if (8 * i + e < D) acc |= (uint32_t)nearest_centre(x[8 * i + e], ch) << (4 * e);
+        w[i] = acc;
+    }
+    if (!live) return;
+    store_codebook(c, a.centroids_f16 + row * kK);
+    uint8_t* out = a.idx + row * (D / 2);
+    if (a.vec_stores >= 1) {
+        uint32_t* o = reinterpret_cast<uint32_t*>(out);
+#pragma unroll
+        for (int i = 0; i < NWORDS; ++i) o[i] = w[i];
+    } else {
+#pragma unroll
+        for (int b = 0; b < D / 2; ++b) out[b] = (uint8_t)(w[b / 4] >> (8 * (b % 4)));
+    }
+}
+
+// Launches the register-resident kernel for `dim` if there is one; returns false otherwise.
+template <typename Tin>
+inline bool launch_kmeans16_rpl(const KMeansArgs& a, int32_t dim, hipStream_t stream)
+{
+    const dim3 grid((unsigned)((a.rows + 63) / 64)), block(64);
+    switch (dim) {
+#define E4Q_CASE(D) \
+    case D:         \
+        hipLaunchKernelGGL((kmeans16_rpl_kernel<D, Tin>), grid, block, 0, stream, a); \
+        return true;
+        E4Q_CASE(24) E4Q_CASE(32) E4Q_CASE(40) E4Q_CASE(48) E4Q_CASE(56) E4Q_CASE(64) E4Q_CASE(72)
+        E4Q_CASE(80) E4Q_CASE(88) E4Q_CASE(96) E4Q_CASE(104) E4Q_CASE(112) E4Q_CASE(120) E4Q_CASE(128)
+#undef E4Q_CASE
+        default:
+            return false;
+    }
+}
+
+}  // namespace e4q

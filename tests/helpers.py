@@ -22,3 +22,14 @@ def f16_bits(t):
     import torch
 
     return t.cpu().view(torch.int16).numpy().view(np.uint16)
+
+
+def oracle_kmeans_in_parallel(oracle, table: np.ndarray, lloyd_iters: int, threads: int = 0):
+    """The codebook oracle on a large table, rows split over host threads."""
+    threads = threads or max(1, min(16, len(os.sched_getaffinity(0))))
+    rows = table.shape[0]
+    bounds = [rows * k // threads for k in range(threads + 1)]
+    with ThreadPoolExecutor(max_workers=threads) as pool:
+        parts = list(pool.map(lambda k: oracle.quantize_rowwise_kmeans16(table[bounds[k]:bounds[k + 1]], lloyd_iters),
+                              range(threads)))
+    return tuple(np.concatenate([p[i] for p in parts]) for i in range(2))

@@ -30,7 +30,8 @@ def declared_functions():
 def test_header_declares_the_expected_entry_points():
     names = declared_functions()
     for must in ["e4q_quantize_rowwise_greedy", "e4q_dequantize", "e4q_quantize_rowwise_greedy_batch",
-                 "e4q_greedy_iterations", "e4q_strerror", "e4q_last_hip_error", "e4q_version"]:
+                 "e4q_greedy_iterations", "e4q_strerror", "e4q_last_hip_error", "e4q_version",
+                 "e4q_quantize_rowwise_kmeans16", "e4q_dequantize_codebook"]:
         assert must in names
 
 
@@ -101,6 +102,19 @@ def test_validation_rejects_bad_arguments_before_any_launch(lib):
     assert dq(None, p, p, 10, 64, 4, p, None) == -1
     assert dq(p, p, p, 10, 64, 4, None, None) == -1
     assert dq(None, None, None, 0, 64, 4, None, None) == 0
+
+    km = lib.e4q_quantize_rowwise_kmeans16
+    assert km(p, 0, 10, 64, 64, -1, p, p, None) == -4
+    assert km(p, 3, 10, 64, 64, 20, p, p, None) == -5
+    assert km(p, 0, 10, 0, 64, 20, p, p, None) == -2
+    assert km(p, 0, 10, 64, 32, 20, p, p, None) == -2
+    assert km(None, 0, 10, 64, 64, 20, p, p, None) == -1
+    assert km(p, 0, 10, 64, 64, 20, p, None, None) == -1
+    assert km(None, 0, 0, 64, 64, 20, None, None, None) == 0
+    dc = lib.e4q_dequantize_codebook
+    assert dc(p, p, -1, 64, p, None) == -2
+    assert dc(p, None, 10, 64, p, None) == -1
+    assert dc(None, None, 0, 64, None, None) == 0
 
     from paper_1911_02079_amd.binding import TableDesc
 

@@ -4,7 +4,7 @@ TEST INFRASTRUCTURE ONLY: the test-suite, the smoke check and the benchmark's
 CPU-baseline leg are the only callers.  The HIP library never imports this
 package and this package never imports the HIP binding.
 
-`oracle.build()` compiles `e4q_oracle.c` and `e4q_oracle_kmeans.c` with gcc into `libe4q_oracle.so`
+`oracle.build()` compiles `e4q_oracle.c`, `e4q_oracle_kmeans.c` and `e4q_oracle_sls.c` with gcc into `libe4q_oracle.so`
 next to it; the functions below are thin ctypes wrappers taking and returning
 NumPy arrays.  See the header of `e4q_oracle.c` for what is computed and which
 passages of the paper each step follows.
@@ -18,7 +18,7 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRCS = [os.path.join(_HERE, "e4q_oracle.c"), os.path.join(_HERE, "e4q_oracle_kmeans.c")]
+_SRCS = [os.path.join(_HERE, f) for f in ("e4q_oracle.c", "e4q_oracle_kmeans.c", "e4q_oracle_sls.c")]
 _LIB_PATH = os.path.join(_HERE, "libe4q_oracle.so")
 _lib = None
 
@@ -69,6 +69,9 @@ def _load():
     lib.e4q_oracle_dequantize_codebook.argtypes = [c.c_void_p, c.c_void_p, c.c_int64, c.c_int32,
                                                    c.c_void_p]
     lib.e4q_oracle_dequantize_codebook.restype = c.c_int
+    lib.e4q_oracle_sparse_lengths_sum.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_int64, c.c_int32,
+                                                  c.c_void_p, c.c_void_p, c.c_int64, c.c_void_p]
+    lib.e4q_oracle_sparse_lengths_sum.restype = c.c_int
     _lib = lib
     return lib
 
@@ -192,6 +195,26 @@ def dequantize_codebook(idx: np.ndarray, centroids_f16: np.ndarray, dim: int) ->
     assert idx.shape[1] == (dim + 1) // 2 and centroids_f16.shape == (rows, 16)
     out = np.empty((rows, dim), dtype=np.float32)
     rc = _load().e4q_oracle_dequantize_codebook(_ptr(idx), _ptr(centroids_f16), rows, dim, _ptr(out))
+    if rc != 0:
+        raise ValueError("oracle rejected the arguments")
+    return out
+
+
+def sparse_lengths_sum(codes: np.ndarray, scale_f16: np.ndarray, bias_f16: np.ndarray, dim: int,
+                       indices: np.ndarray, offsets: np.ndarray) -> np.ndarray:
+    """4-bit SparseLengthsSum (Section 4): out[b] = sum of the de-quantized rows indices[offsets[b]:offsets[b+1]],
+    accumulated left to right in binary32.  Returns float32 [n_bags, dim]."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    scale_f16 = np.ascontiguousarray(scale_f16, dtype=np.uint16)
+    bias_f16 = np.ascontiguousarray(bias_f16, dtype=np.uint16)
+    indices = np.ascontiguousarray(indices, dtype=np.int64)
+    offsets = np.ascontiguousarray(offsets, dtype=np.int64)
+    n_bags = offsets.size - 1
+    assert n_bags >= 0 and (n_bags == 0 or (offsets[0] >= 0 and offsets[-1] <= indices.size))
+    assert np.all(np.diff(offsets) >= 0)
+    out = np.empty((n_bags, dim), dtype=np.float32)
+    rc = _load().e4q_oracle_sparse_lengths_sum(_ptr(codes), _ptr(scale_f16), _ptr(bias_f16), codes.shape[0], dim,
+                                               _ptr(indices), _ptr(offsets), n_bags, _ptr(out))
     if rc != 0:
         raise ValueError("oracle rejected the arguments")
     return out

@@ -29,6 +29,16 @@ KMEANS_MUTANTS = {
     "squared_distance_sign": ("float dk = fabsf(x - c[k]);", "float dk = x - c[k];"),
 }
 
+SLS_MUTANTS = {
+    "nibbles_swapped": ("unsigned q = (k & 1) ? (byte >> 4) : (byte & 0xfu);", "unsigned q = (k & 1) ? (byte & 0xfu) : (byte >> 4);"),
+    "bag_starts_one_late": ("for (int64_t i = offsets[b]; i < offsets[b + 1]; ++i) {", "for (int64_t i = offsets[b] + 1; i < offsets[b + 1]; ++i) {"),
+    "bag_runs_one_over": ("i < offsets[b + 1]; ++i) {", "i <= offsets[b + 1]; ++i) {"),
+    "right_to_left": ("for (int64_t i = offsets[b]; i < offsets[b + 1]; ++i) {", "for (int64_t i = offsets[b + 1] - 1; i >= offsets[b]; --i) {"),
+    "bias_dropped": ("e4q_oracle_f16_to_f32(bias_f16[r]));", "0.0f);"),
+    "last_row_rejected": ("if (r < 0 || r >= rows) continue;", "if (r < 0 || r >= rows - 1) continue;"),
+    "scale_of_wrong_row": ("e4q_oracle_f16_to_f32(scale_f16[r])", "e4q_oracle_f16_to_f32(scale_f16[b])"),
+}
+
 MUTANTS = {
     "sixteen_levels": ("#define E4Q_QMAX 15.0f", "#define E4Q_QMAX 16.0f"),
     "tie_moves_lower_bound": ("if (loss_l < loss_r) {", "if (loss_l <= loss_r) {"),
@@ -70,7 +80,7 @@ def test_pins_catch_planted_mistake(name, tmp_path):
     old, new = MUTANTS[name]
     dst = tmp_path / "oracle"
     dst.mkdir()
-    for f in ("__init__.py", "numpy_twin.py", "e4q_oracle.c", "e4q_oracle_kmeans.c"):
+    for f in ("__init__.py", "numpy_twin.py", "e4q_oracle.c", "e4q_oracle_kmeans.c", "e4q_oracle_sls.c"):
         shutil.copy(os.path.join(ROOT, "oracle", f), dst / f)
     src = (dst / "e4q_oracle.c").read_text()
     assert src.count(old) >= 1, f"mutation site for {name} no longer exists in the oracle"
@@ -85,10 +95,24 @@ def test_kmeans_pins_catch_planted_mistake(name, tmp_path):
     old, new = KMEANS_MUTANTS[name]
     dst = tmp_path / "oracle"
     dst.mkdir()
-    for f in ("__init__.py", "numpy_twin.py", "e4q_oracle.c", "e4q_oracle_kmeans.c"):
+    for f in ("__init__.py", "numpy_twin.py", "e4q_oracle.c", "e4q_oracle_kmeans.c", "e4q_oracle_sls.c"):
         shutil.copy(os.path.join(ROOT, "oracle", f), dst / f)
     src = (dst / "e4q_oracle_kmeans.c").read_text()
     assert src.count(old) >= 1, f"mutation site for {name} no longer exists in the oracle"
     (dst / "e4q_oracle_kmeans.c").write_text(src.replace(old, new, 1))
     res = _run_pins(str(tmp_path), "test_oracle_kmeans_pins.py")
+    assert res.returncode != 0, f"pins did not notice mutant '{name}':\n{res.stdout[-2000:]}"
+
+
+@pytest.mark.parametrize("name", sorted(SLS_MUTANTS))
+def test_sls_pins_catch_planted_mistake(name, tmp_path):
+    old, new = SLS_MUTANTS[name]
+    dst = tmp_path / "oracle"
+    dst.mkdir()
+    for f in ("__init__.py", "numpy_twin.py", "e4q_oracle.c", "e4q_oracle_kmeans.c", "e4q_oracle_sls.c"):
+        shutil.copy(os.path.join(ROOT, "oracle", f), dst / f)
+    src = (dst / "e4q_oracle_sls.c").read_text()
+    assert src.count(old) >= 1, f"mutation site for {name} no longer exists in the oracle"
+    (dst / "e4q_oracle_sls.c").write_text(src.replace(old, new, 1))
+    res = _run_pins(str(tmp_path), "test_oracle_sls_pins.py")
     assert res.returncode != 0, f"pins did not notice mutant '{name}':\n{res.stdout[-2000:]}"

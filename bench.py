@@ -7,7 +7,9 @@ Default workload (the one the headline metric is quoted on): row-wise greedy 4-b
 of a seeded synthetic 10 M x 128 fp32 table, then de-quantization of the result.  One "step" is
 one pass of the whole path over the table, which is already resident in HBM: the quantizer (row
 load, min/max, Algorithm 1's search, encode + pack, binary16 scale/bias) followed by the
-de-quantizer.  `--workload mixture_2M_x_64_kmeans16` times the codebook variant the same way.
+de-quantizer.  `--workload mixture_2M_x_64_kmeans16` times the codebook variant the same way;
+`--workload lookup_10M_x_128_sls` times the 4-bit SparseLengthsSum lookup over the quantized
+table (2^20 bags of 1..64 uniformly random rows; bound by HBM gathers).
 
 Prints ONE JSON line.  `value` is rows per second over whole steps; `kernels` gives each kernel's
 own average duration from HIP events recorded on the launch stream inside the timed region;
@@ -40,6 +42,7 @@ WORKLOADS = {
     "outlier_1M_x_64": ("greedy", "outlier_table", 1_000_000, 64, {"n_bins": 200, "ratio": 0.16}),
     "laplace_10M_x_128": ("greedy", "laplace_offset_table", 10_000_000, 128, {"n_bins": 200, "ratio": 0.16}),
     "mixture_2M_x_64_kmeans16": ("kmeans16", "mixture_table", 2_000_000, 64, {"lloyd_iters": 20}),
+    "lookup_10M_x_128_sls": ("sls", "laplace_offset_table", 10_000_000, 128, {"n_bags": 1 << 20, "max_len": 64}),
 }
 
 
@@ -93,6 +96,111 @@ def cpu_baseline(table_gpu, run_oracle, target_seconds: float = 12.0):
                       f"{dt:.1f} s wall; single-thread probe {1e6 * per_row:.1f} us/row"}
 
 
+def bench_sls(args, e4q, synth, torch, gen, rows, dim, params) -> int:
+    """The lookup operator on the quantized table: one step = one e4q_sparse_lengths_sum call."""
+    import numpy as np
+
+    table = getattr(synth, gen)(rows, dim, device="cuda:0")
+    codes, scale, bias = e4q.quantize_rowwise_greedy(table, 200, 0.16)
+    del table
+    n_bags = params["n_bags"]
+    indices, offsets = synth.lookup_bags(rows, n_bags, 1, params["max_len"], device="cuda:0")
+    n_lookups = indices.numel()
+    out = torch.empty((n_bags, dim), dtype=torch.float32, device="cuda:0")
+    pitch = e4q.fused_row_bytes(dim)
+    fused = e4q.fuse_rows(codes, scale, bias, dim, pitch)  # one-off re-layout of the table, not timed
+    run = lambda: e4q.sparse_lengths_sum_fused(fused, dim, indices, offsets, out=out)  # noqa: E731
+
+    def side_timing(fn, reps=5):
+        fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    # context, outside the timed region: the same lookup from the three separate arrays, and from
+    # records padded to one 128-byte line each
+    three_ms = side_timing(lambda: e4q.sparse_lengths_sum(codes, scale, bias, dim, indices, offsets, out=out))
+    fused128 = e4q.fuse_rows(codes, scale, bias, dim, 128)
+    line_ms = side_timing(lambda: e4q.sparse_lengths_sum_fused(fused128, dim, indices, offsets, out=out))
+    fuse_ms = side_timing(lambda: e4q.fuse_rows(codes, scale, bias, dim, pitch, out=fused))
+    del fused128
+    for _ in range(args.warmup):
+        run()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        evs[k][0].record()
+        run()
+        evs[k][1].record()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    if args.calibrate_copy:
+        src = torch.ones(1 << 28, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+    ms = sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps
+    # per looked-up row: d/2 bytes of codes, 2 + 2 bytes of parameters, 8 bytes of index;
+    # per bag: 4d bytes of output and 8 bytes of offset
+    alg_bytes = n_lookups * (dim // 2 + 4 + indices.element_size()) + n_bags * (4 * dim + 8)
+    sums = n_lookups * dim
+    result = {
+        "metric": "billion sums/sec (INT4 SparseLengthsSum)", "value": sums / (elapsed / args.steps) / 1e9,
+        "unit": "G sums/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": 1e3 * elapsed / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "rows": rows, "dim": dim, "n_bags": n_bags, "lookups": n_lookups,
+                   "bag_lengths": f"uniform 1..{params['max_len']}", "index_dtype": "int64",
+                   "step": "sparse_lengths_sum_fused over all bags, fused records of 68 bytes resident in HBM "
+                           "(680 MB, not cache resident)"},
+        "kernels": {"sls_fused_w8_kernel": {"avg_ms": ms, "lookups_per_s": n_lookups / (ms * 1e-3),
+                                            "G_sums_per_s": sums / (ms * 1e-3) / 1e9, "row_pitch": pitch},
+                    "sls_fused_w8_kernel (row_pitch 128)": {"avg_ms": line_ms},
+                    "sls_w8_kernel (separate codes / scale / bias arrays)": {"avg_ms": three_ms},
+                    "fuse_rows_w_kernel": {"avg_ms": fuse_ms}},
+        "roofline": {"kernel": "sls_fused_w8_kernel", "bound": "hbm", "achieved": alg_bytes / (ms * 1e-3) / 1e9,
+                     "peak": PEAK_HBM_BYTES / 1e9, "unit": "GB/s", "frac": alg_bytes / (ms * 1e-3) / PEAK_HBM_BYTES,
+                     "bytes_per_lookup": dim // 2 + 4 + indices.element_size(), "bytes_per_bag": 4 * dim + 8,
+                     "traffic": read_traffic(f"sls_fused_w8_kernel_{args.workload}_hbm_traffic.txt")},
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+
+        cores = max(1, min(16, len(os.sched_getaffinity(0))))
+        sample_bags = min(n_bags, 262_144)
+        off = offsets[: sample_bags + 1].cpu().numpy()
+        idx = indices[: int(off[-1])].cpu().numpy()
+        used, inv = np.unique(idx, return_inverse=True)
+        sub = torch.from_numpy(used).cuda()
+        s_codes = codes[sub].cpu().numpy()
+        s_scale = scale[sub].cpu().view(torch.int16).numpy().view(np.uint16)
+        s_bias = bias[sub].cpu().view(torch.int16).numpy().view(np.uint16)
+        inv = inv.astype(np.int64)
+        bounds = [sample_bags * k // cores for k in range(cores + 1)]
+
+        def part(k):
+            o = off[bounds[k]:bounds[k + 1] + 1]
+            return oracle.sparse_lengths_sum(s_codes, s_scale, s_bias, dim, inv[o[0]:o[-1]], o - o[0])
+
+        t0 = time.perf_counter()
+        with ThreadPoolExecutor(max_workers=cores) as pool:
+            list(pool.map(part, range(cores)))
+        dt = time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": int(off[-1]) * dim / dt / 1e9, "unit": "G sums/s", "cores": cores,
+                                  "kind": "oracle", "sample": f"first {sample_bags} bags ({int(off[-1])} lookups) over "
+                                  f"the rows they touch, bags split over {cores} threads, {dt:.2f} s wall"}
+    print(json.dumps(result), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -120,6 +228,8 @@ def main() -> int:
     e4q.binding.load_library()
     torch.cuda.set_device(0)
     method, gen, rows, dim, params = WORKLOADS[args.workload]
+    if method == "sls":
+        return bench_sls(args, e4q, synth, torch, gen, rows, dim, params)
 
     table = getattr(synth, gen)(rows, dim, device="cuda:0")
     xh = torch.empty((rows, dim), dtype=torch.float32, device=table.device)

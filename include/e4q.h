@@ -39,7 +39,7 @@ extern "C" {
 #define E4Q_ERR_BAD_SHAPE (-2)      /* rows < 0, dim <= 0, dim > E4Q_MAX_DIM, row_stride < dim */
 #define E4Q_ERR_BAD_NBITS (-3)      /* nbits != 4 */
 #define E4Q_ERR_BAD_SEARCH (-4)     /* n_bins < 1, ratio outside [0, 1), ratio NaN, lloyd_iters < 0 */
-#define E4Q_ERR_BAD_DTYPE (-5)      /* dtype is neither E4Q_F32 nor E4Q_F16 */
+#define E4Q_ERR_BAD_DTYPE (-5)      /* dtype is neither E4Q_F32 nor E4Q_F16; index_bytes is neither 4 nor 8 */
 #define E4Q_ERR_LAUNCH (-6)         /* HIP reported an error when the kernel was enqueued */
 #define E4Q_ERR_BAD_ALIGNMENT (-7)  /* table pointer not aligned to its element size */
 
@@ -143,6 +143,48 @@ int e4q_quantize_rowwise_kmeans16(const void* table, int dtype, int64_t rows, in
  */
 int e4q_dequantize_codebook(const uint8_t* idx, const uint16_t* centroids_f16, int64_t rows, int32_t dim,
                             float* out, void* hip_stream);
+
+/*
+ * 4-bit SparseLengthsSum: the pooled embedding lookup that reads the quantized table (Section 4,
+ * "Efficient 4-bit Embedding Operation Implementation", Table 1).  Bag b owns
+ * indices[offsets[b] .. offsets[b+1]); out[b][k] = sum over the bag of scale[r] * code[r][k] + bias[r],
+ * accumulated from +0 in index order in binary32 (the de-quantizer is one fused multiply-add, the
+ * accumulation a separate add).  An empty bag gives zeros; an index outside [0, rows) adds
+ * nothing; offsets are clamped to [0, n_indices], so malformed offsets cannot cause a fault.
+ *
+ *   codes, scale_f16, bias_f16  [in]  the table, as written by e4q_quantize_rowwise_greedy
+ *   indices      [in]  n_indices row numbers, int32 (index_bytes = 4) or int64 (index_bytes = 8)
+ *   offsets      [in]  n_bags + 1 int64 values, non-decreasing: the exclusive prefix sum of the
+ *                      operator's LENGTHS input
+ *   out          [out] n_bags x dim binary32, dense
+ */
+int e4q_sparse_lengths_sum(const uint8_t* codes, const uint16_t* scale_f16, const uint16_t* bias_f16,
+                           int64_t rows, int32_t dim, int32_t nbits, const void* indices, int32_t index_bytes,
+                           int64_t n_indices, const int64_t* offsets, int64_t n_bags, float* out,
+                           void* hip_stream);
+
+/*
+ * Fused lookup records.  A lookup of one row needs its codes, its scale and its bias; kept in
+ * three arrays they sit in three different places of HBM.  e4q_fuse_rows copies a quantized table
+ * into one record per row, `row_pitch` bytes apart (as the lookup operator of Section 4 reads it):
+ *     [ codes: ceil(dim/2) bytes ][ pad to an even offset ][ scale f16 ][ bias f16 ][ pad: zeros ]
+ * e4q_fused_row_bytes(dim) is the smallest record (dim/2 + 4 for even dim/2: the d/2 + 4 bytes per
+ * row behind Table 3's sizes); row_pitch must be even and at least that (for example 128 to give
+ * every record of a dim-128 table its own 128-byte line).  Host-only helper; negative on bad dim.
+ *
+ *   fused  [out] rows * row_pitch bytes
+ */
+int64_t e4q_fused_row_bytes(int32_t dim);
+int e4q_fuse_rows(const uint8_t* codes, const uint16_t* scale_f16, const uint16_t* bias_f16, int64_t rows,
+                  int32_t dim, int32_t nbits, int64_t row_pitch, uint8_t* fused, void* hip_stream);
+
+/*
+ * e4q_sparse_lengths_sum over fused records (same arithmetic, same result bit for bit; about one
+ * half to one third of the HBM traffic per lookup).
+ */
+int e4q_sparse_lengths_sum_fused(const uint8_t* fused, int64_t rows, int32_t dim, int32_t nbits, int64_t row_pitch,
+                                 const void* indices, int32_t index_bytes, int64_t n_indices,
+                                 const int64_t* offsets, int64_t n_bags, float* out, void* hip_stream);
 
 /*
  * n_iter = ceil(n_bins * ratio) clamped to [0, n_bins - 1]: the number of trips of the loop of

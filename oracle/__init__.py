@@ -72,6 +72,9 @@ def _load():
     lib.e4q_oracle_sparse_lengths_sum.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_int64, c.c_int32,
                                                   c.c_void_p, c.c_void_p, c.c_int64, c.c_void_p]
     lib.e4q_oracle_sparse_lengths_sum.restype = c.c_int
+    lib.e4q_oracle_fuse_rows.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_int64, c.c_int32, c.c_int64,
+                                         c.c_void_p]
+    lib.e4q_oracle_fuse_rows.restype = c.c_int
     _lib = lib
     return lib
 
@@ -215,6 +218,19 @@ def sparse_lengths_sum(codes: np.ndarray, scale_f16: np.ndarray, bias_f16: np.nd
     out = np.empty((n_bags, dim), dtype=np.float32)
     rc = _load().e4q_oracle_sparse_lengths_sum(_ptr(codes), _ptr(scale_f16), _ptr(bias_f16), codes.shape[0], dim,
                                                _ptr(indices), _ptr(offsets), n_bags, _ptr(out))
+    if rc != 0:
+        raise ValueError("oracle rejected the arguments")
+    return out
+
+
+def fuse_rows(codes: np.ndarray, scale_f16: np.ndarray, bias_f16: np.ndarray, dim: int, row_pitch: int) -> np.ndarray:
+    """Records of `row_pitch` bytes: codes, then (at the next even offset) binary16 scale and bias."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    scale_f16 = np.ascontiguousarray(scale_f16, dtype=np.uint16)
+    bias_f16 = np.ascontiguousarray(bias_f16, dtype=np.uint16)
+    rows = codes.shape[0]
+    out = np.full((rows, row_pitch), 0xEE, dtype=np.uint8)
+    rc = _load().e4q_oracle_fuse_rows(_ptr(codes), _ptr(scale_f16), _ptr(bias_f16), rows, dim, row_pitch, _ptr(out))
     if rc != 0:
         raise ValueError("oracle rejected the arguments")
     return out

@@ -49,3 +49,30 @@ int e4q_oracle_sparse_lengths_sum(const uint8_t *codes, const uint16_t *scale_f1
     }
     return 0;
 }
+
+/*
+ * Fused row layout for lookups: one record per row, `row_pitch` bytes apart, holding the row's
+ * packed codes followed (at the next even offset) by its binary16 scale and bias -- everything a
+ * lookup of that row needs sits in one place, as in the operator of Section 4.
+ *   record = [ codes: ceil(dim/2) bytes ][ pad to even ][ scale: 2 bytes ][ bias: 2 bytes ][ pad ]
+ * Padding bytes are written as 0.  Returns -1 if row_pitch is odd or too small.
+ */
+int e4q_oracle_fuse_rows(const uint8_t *codes, const uint16_t *scale_f16, const uint16_t *bias_f16,
+                         int64_t rows, int32_t dim, int64_t row_pitch, uint8_t *fused)
+{
+    int64_t nbytes = (dim + 1) / 2;
+    int64_t params_at = (nbytes + 1) & ~(int64_t)1;
+    if (!codes || !scale_f16 || !bias_f16 || !fused || rows < 0 || dim <= 0 || (row_pitch & 1) ||
+        row_pitch < params_at + 4)
+        return -1;
+    for (int64_t r = 0; r < rows; ++r) {
+        uint8_t *rec = fused + r * row_pitch;
+        for (int64_t k = 0; k < row_pitch; ++k) rec[k] = 0;
+        for (int64_t k = 0; k < nbytes; ++k) rec[k] = codes[r * nbytes + k];
+        rec[params_at + 0] = (uint8_t)(scale_f16[r] & 0xff);
+        rec[params_at + 1] = (uint8_t)(scale_f16[r] >> 8);
+        rec[params_at + 2] = (uint8_t)(bias_f16[r] & 0xff);
+        rec[params_at + 3] = (uint8_t)(bias_f16[r] >> 8);
+    }
+    return 0;
+}

@@ -8,7 +8,8 @@ the built library) and seeded synthetic-table generators (`synth.py`).
 from . import synth  # noqa: F401
 
 __all__ = ["synth", "binding", "quantize_rowwise_greedy", "quantize_rowwise_greedy_batch", "dequantize",
-           "greedy_iterations", "quantize_rowwise_kmeans16", "dequantize_codebook"]
+           "greedy_iterations", "quantize_rowwise_kmeans16", "dequantize_codebook", "sparse_lengths_sum",
+           "fuse_rows", "sparse_lengths_sum_fused", "fused_row_bytes"]
 
 
 def __getattr__(name):
@@ -17,7 +18,8 @@ def __getattr__(name):
 
         return importlib.import_module(".binding", __name__)
     if name in ("quantize_rowwise_greedy", "quantize_rowwise_greedy_batch", "dequantize", "greedy_iterations",
-                "alloc_outputs", "load_library", "E4QError", "quantize_rowwise_kmeans16", "dequantize_codebook"):
+                "alloc_outputs", "load_library", "E4QError", "quantize_rowwise_kmeans16", "dequantize_codebook",
+                "sparse_lengths_sum", "fuse_rows", "sparse_lengths_sum_fused", "fused_row_bytes"):
         import importlib
 
         return getattr(importlib.import_module(".binding", __name__), name)

@@ -59,6 +59,18 @@ def load_library() -> ctypes.CDLL:
     lib.e4q_quantize_rowwise_kmeans16.restype = c.c_int
     lib.e4q_dequantize_codebook.argtypes = [c.c_void_p, c.c_void_p, c.c_int64, c.c_int32, c.c_void_p, c.c_void_p]
     lib.e4q_dequantize_codebook.restype = c.c_int
+    lib.e4q_sparse_lengths_sum.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_int64, c.c_int32, c.c_int32,
+                                           c.c_void_p, c.c_int32, c.c_int64, c.c_void_p, c.c_int64, c.c_void_p,
+                                           c.c_void_p]
+    lib.e4q_sparse_lengths_sum.restype = c.c_int
+    lib.e4q_fused_row_bytes.argtypes = [c.c_int32]
+    lib.e4q_fused_row_bytes.restype = c.c_int64
+    lib.e4q_fuse_rows.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_int64, c.c_int32, c.c_int32, c.c_int64,
+                                  c.c_void_p, c.c_void_p]
+    lib.e4q_fuse_rows.restype = c.c_int
+    lib.e4q_sparse_lengths_sum_fused.argtypes = [c.c_void_p, c.c_int64, c.c_int32, c.c_int32, c.c_int64, c.c_void_p,
+                                                 c.c_int32, c.c_int64, c.c_void_p, c.c_int64, c.c_void_p, c.c_void_p]
+    lib.e4q_sparse_lengths_sum_fused.restype = c.c_int
     lib.e4q_greedy_iterations.argtypes = [c.c_int32, c.c_float]
     lib.e4q_greedy_iterations.restype = c.c_int32
     lib.e4q_strerror.argtypes = [c.c_int]
@@ -227,5 +239,98 @@ def dequantize_codebook(idx: torch.Tensor, centroids_f16: torch.Tensor, dim: int
     with torch.cuda.device(idx.device):
         rc = lib.e4q_dequantize_codebook(idx.data_ptr(), centroids_f16.data_ptr(), rows, int(dim), out.data_ptr(),
                                          _stream_ptr(stream, idx.device))
+    _check(rc)
+    return out
+
+
+def sparse_lengths_sum(codes: torch.Tensor, scale_f16: torch.Tensor, bias_f16: torch.Tensor, dim: int,
+                       indices: torch.Tensor, offsets: torch.Tensor, nbits: int = 4,
+                       out: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """e4q_sparse_lengths_sum: float32 [n_bags, dim]; `indices` int32 or int64, `offsets` int64 [n_bags + 1]."""
+    lib = load_library()
+    for t in (codes, scale_f16, bias_f16, indices, offsets):
+        if not t.is_cuda:
+            raise ValueError("libe4q works on device memory only")
+        if not t.is_contiguous():
+            raise ValueError("all inputs must be dense")
+    if codes.dtype != torch.uint8 or scale_f16.dtype != torch.float16 or bias_f16.dtype != torch.float16:
+        raise TypeError("codes must be uint8, scale and bias float16")
+    if indices.dtype not in (torch.int32, torch.int64) or offsets.dtype != torch.int64:
+        raise TypeError("indices must be int32 or int64 and offsets int64")
+    rows = codes.shape[0]
+    if codes.shape[1] != (dim + 1) // 2 or scale_f16.numel() != rows or bias_f16.numel() != rows:
+        raise ValueError("shapes of codes / scale / bias do not match dim")
+    n_bags = offsets.numel() - 1
+    if n_bags < 0:
+        raise ValueError("offsets needs n_bags + 1 entries")
+    if out is None:
+        out = torch.empty((n_bags, dim), dtype=torch.float32, device=codes.device)
+    elif out.dtype != torch.float32 or not out.is_contiguous() or tuple(out.shape) != (n_bags, dim):
+        raise ValueError("out must be a dense float32 [n_bags, dim] tensor")
+    with torch.cuda.device(codes.device):
+        rc = lib.e4q_sparse_lengths_sum(codes.data_ptr(), scale_f16.data_ptr(), bias_f16.data_ptr(), rows, int(dim),
+                                        int(nbits), indices.data_ptr(), indices.element_size(), indices.numel(),
+                                        offsets.data_ptr(), n_bags, out.data_ptr(), _stream_ptr(stream, codes.device))
+    _check(rc)
+    return out
+
+
+def fused_row_bytes(dim: int) -> int:
+    n = int(load_library().e4q_fused_row_bytes(int(dim)))
+    if n < 0:
+        _check(n)
+    return n
+
+
+def fuse_rows(codes: torch.Tensor, scale_f16: torch.Tensor, bias_f16: torch.Tensor, dim: int,
+              row_pitch: Optional[int] = None, nbits: int = 4, out: Optional[torch.Tensor] = None,
+              stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """e4q_fuse_rows: uint8 [rows, row_pitch] records (codes, then scale and bias)."""
+    lib = load_library()
+    if not (codes.is_cuda and scale_f16.is_cuda and bias_f16.is_cuda):
+        raise ValueError("libe4q works on device memory only")
+    if codes.dtype != torch.uint8 or scale_f16.dtype != torch.float16 or bias_f16.dtype != torch.float16:
+        raise TypeError("codes must be uint8, scale and bias float16")
+    if not (codes.is_contiguous() and scale_f16.is_contiguous() and bias_f16.is_contiguous()):
+        raise ValueError("codes, scale and bias must be dense")
+    rows = codes.shape[0]
+    if codes.shape[1] != (dim + 1) // 2 or scale_f16.numel() != rows or bias_f16.numel() != rows:
+        raise ValueError("shapes of codes / scale / bias do not match dim")
+    pitch = int(row_pitch) if row_pitch is not None else fused_row_bytes(dim)
+    if out is None:
+        out = torch.empty((rows, pitch), dtype=torch.uint8, device=codes.device)
+    elif out.dtype != torch.uint8 or not out.is_contiguous() or tuple(out.shape) != (rows, pitch):
+        raise ValueError("out must be a dense uint8 [rows, row_pitch] tensor")
+    with torch.cuda.device(codes.device):
+        rc = lib.e4q_fuse_rows(codes.data_ptr(), scale_f16.data_ptr(), bias_f16.data_ptr(), rows, int(dim), int(nbits),
+                               pitch, out.data_ptr(), _stream_ptr(stream, codes.device))
+    _check(rc)
+    return out
+
+
+def sparse_lengths_sum_fused(fused: torch.Tensor, dim: int, indices: torch.Tensor, offsets: torch.Tensor,
+                             nbits: int = 4, out: Optional[torch.Tensor] = None,
+                             stream: Optional[torch.cuda.Stream] = None) -> torch.Tensor:
+    """e4q_sparse_lengths_sum_fused on records written by fuse_rows (row pitch = fused.shape[1])."""
+    lib = load_library()
+    for t in (fused, indices, offsets):
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError("libe4q works on dense device memory only")
+    if fused.dtype != torch.uint8 or fused.dim() != 2:
+        raise TypeError("fused must be a uint8 [rows, row_pitch] tensor")
+    if indices.dtype not in (torch.int32, torch.int64) or offsets.dtype != torch.int64:
+        raise TypeError("indices must be int32 or int64 and offsets int64")
+    rows, pitch = fused.shape
+    n_bags = offsets.numel() - 1
+    if n_bags < 0:
+        raise ValueError("offsets needs n_bags + 1 entries")
+    if out is None:
+        out = torch.empty((n_bags, dim), dtype=torch.float32, device=fused.device)
+    elif out.dtype != torch.float32 or not out.is_contiguous() or tuple(out.shape) != (n_bags, dim):
+        raise ValueError("out must be a dense float32 [n_bags, dim] tensor")
+    with torch.cuda.device(fused.device):
+        rc = lib.e4q_sparse_lengths_sum_fused(fused.data_ptr(), rows, int(dim), int(nbits), pitch, indices.data_ptr(),
+                                              indices.element_size(), indices.numel(), offsets.data_ptr(), n_bags,
+                                              out.data_ptr(), _stream_ptr(stream, fused.device))
     _check(rc)
     return out

@@ -187,15 +187,76 @@ int e4q_dequantize_codebook(const uint8_t* idx, const uint16_t* centroids_f16, i
     return err == hipSuccess ? E4Q_OK : fail_launch(err);
 }
 
+int e4q_sparse_lengths_sum(const uint8_t* codes, const uint16_t* scale_f16, const uint16_t* bias_f16,
+                           int64_t rows, int32_t dim, int32_t nbits, const void* indices, int32_t index_bytes,
+                           int64_t n_indices, const int64_t* offsets, int64_t n_bags, float* out,
+                           void* hip_stream)
+{
+    if (nbits != 4) return E4Q_ERR_BAD_NBITS;
+    if (index_bytes != 4 && index_bytes != 8) return E4Q_ERR_BAD_DTYPE;
+    if (rows < 0 || dim <= 0 || dim > E4Q_MAX_DIM || n_indices < 0 || n_bags < 0) return E4Q_ERR_BAD_SHAPE;
+    if (n_bags == 0) return E4Q_OK;
+    if (!offsets || !out || (n_indices > 0 && !indices)) return E4Q_ERR_NULL_POINTER;
+    if (rows > 0 && (!codes || !scale_f16 || !bias_f16)) return E4Q_ERR_NULL_POINTER;
+    if (!aligned(scale_f16, 2) || !aligned(bias_f16, 2) || !aligned(out, 4) || !aligned(offsets, 8) ||
+        !aligned(indices, (size_t)index_bytes))
+        return E4Q_ERR_BAD_ALIGNMENT;
+    const hipError_t err = e4q::launch_sparse_lengths_sum(codes, scale_f16, bias_f16, rows, dim, indices, index_bytes,
+                                                          n_indices, offsets, n_bags, out,
+                                                          static_cast<hipStream_t>(hip_stream));
+    return err == hipSuccess ? E4Q_OK : fail_launch(err);
+}
+
+static int64_t fused_min_pitch(int32_t dim) { return ((((int64_t)dim + 1) / 2 + 1) & ~(int64_t)1) + 4; }
+
+int64_t e4q_fused_row_bytes(int32_t dim)
+{
+    if (dim <= 0 || dim > E4Q_MAX_DIM) return E4Q_ERR_BAD_SHAPE;
+    return fused_min_pitch(dim);
+}
+
+int e4q_fuse_rows(const uint8_t* codes, const uint16_t* scale_f16, const uint16_t* bias_f16, int64_t rows,
+                  int32_t dim, int32_t nbits, int64_t row_pitch, uint8_t* fused, void* hip_stream)
+{
+    if (nbits != 4) return E4Q_ERR_BAD_NBITS;
+    if (rows < 0 || dim <= 0 || dim > E4Q_MAX_DIM || (row_pitch & 1) || row_pitch < fused_min_pitch(dim))
+        return E4Q_ERR_BAD_SHAPE;
+    if (rows == 0) return E4Q_OK;
+    if (!codes || !scale_f16 || !bias_f16 || !fused) return E4Q_ERR_NULL_POINTER;
+    if (!aligned(scale_f16, 2) || !aligned(bias_f16, 2) || !aligned(fused, 2)) return E4Q_ERR_BAD_ALIGNMENT;
+    const hipError_t err = e4q::launch_fuse_rows(codes, scale_f16, bias_f16, rows, dim, row_pitch, fused,
+                                                 static_cast<hipStream_t>(hip_stream));
+    return err == hipSuccess ? E4Q_OK : fail_launch(err);
+}
+
+int e4q_sparse_lengths_sum_fused(const uint8_t* fused, int64_t rows, int32_t dim, int32_t nbits, int64_t row_pitch,
+                                 const void* indices, int32_t index_bytes, int64_t n_indices,
+                                 const int64_t* offsets, int64_t n_bags, float* out, void* hip_stream)
+{
+    if (nbits != 4) return E4Q_ERR_BAD_NBITS;
+    if (index_bytes != 4 && index_bytes != 8) return E4Q_ERR_BAD_DTYPE;
+    if (rows < 0 || dim <= 0 || dim > E4Q_MAX_DIM || n_indices < 0 || n_bags < 0 || (row_pitch & 1) ||
+        row_pitch < fused_min_pitch(dim))
+        return E4Q_ERR_BAD_SHAPE;
+    if (n_bags == 0) return E4Q_OK;
+    if (!offsets || !out || (n_indices > 0 && !indices) || (rows > 0 && !fused)) return E4Q_ERR_NULL_POINTER;
+    if (!aligned(fused, 2) || !aligned(out, 4) || !aligned(offsets, 8) || !aligned(indices, (size_t)index_bytes))
+        return E4Q_ERR_BAD_ALIGNMENT;
+    const hipError_t err = e4q::launch_sparse_lengths_sum_fused(fused, rows, dim, row_pitch, indices, index_bytes,
+                                                                n_indices, offsets, n_bags, out,
+                                                                static_cast<hipStream_t>(hip_stream));
+    return err == hipSuccess ? E4Q_OK : fail_launch(err);
+}
+
 const char* e4q_strerror(int code)
 {
     switch (code) {
         case E4Q_OK: return "success";
         case E4Q_ERR_NULL_POINTER: return "a required pointer is NULL";
-        case E4Q_ERR_BAD_SHAPE: return "bad shape: need rows >= 0, 0 < dim <= 4096, row_stride >= dim";
+        case E4Q_ERR_BAD_SHAPE: return "bad shape: need rows >= 0, 0 < dim <= 4096, row_stride >= dim, an even row_pitch >= e4q_fused_row_bytes(dim)";
         case E4Q_ERR_BAD_NBITS: return "nbits must be 4";
         case E4Q_ERR_BAD_SEARCH: return "bad search parameters: need n_bins >= 1, 0 <= ratio < 1, lloyd_iters >= 0";
-        case E4Q_ERR_BAD_DTYPE: return "dtype must be E4Q_F32 (0) or E4Q_F16 (1)";
+        case E4Q_ERR_BAD_DTYPE: return "dtype must be E4Q_F32 (0) or E4Q_F16 (1); index_bytes must be 4 or 8";
         case E4Q_ERR_LAUNCH: return "HIP reported an error at kernel launch (see e4q_last_hip_error)";
         case E4Q_ERR_BAD_ALIGNMENT: return "a pointer is not aligned to its element size";
         default: return "unknown e4q error code";

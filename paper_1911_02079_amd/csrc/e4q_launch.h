@@ -47,6 +47,15 @@ struct KMeansArgs {
 hipError_t launch_kmeans16(const KMeansArgs& a, int dtype, int32_t dim, hipStream_t stream);
 hipError_t launch_dequantize_codebook(const uint8_t* idx, const uint16_t* centroids_f16, int64_t rows,
                                       int32_t dim, float* out, hipStream_t stream);
+hipError_t launch_sparse_lengths_sum(const uint8_t* codes, const uint16_t* scale_f16, const uint16_t* bias_f16,
+                                     int64_t rows, int32_t dim, const void* indices, int32_t index_bytes,
+                                     int64_t n_indices, const int64_t* offsets, int64_t n_bags, float* out,
+                                     hipStream_t stream);
+hipError_t launch_fuse_rows(const uint8_t* codes, const uint16_t* scale_f16, const uint16_t* bias_f16, int64_t rows,
+                            int32_t dim, int64_t row_pitch, uint8_t* fused, hipStream_t stream);
+hipError_t launch_sparse_lengths_sum_fused(const uint8_t* fused, int64_t rows, int32_t dim, int64_t row_pitch,
+                                           const void* indices, int32_t index_bytes, int64_t n_indices,
+                                           const int64_t* offsets, int64_t n_bags, float* out, hipStream_t stream);
 hipError_t launch_dequantize(const uint8_t* codes, const uint16_t* scale_f16, const uint16_t* bias_f16,
                              int64_t rows, int32_t dim, float* out, hipStream_t stream);
 

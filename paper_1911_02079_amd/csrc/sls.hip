@@ -1,0 +1,343 @@
+// 4-bit SparseLengthsSum (Section 4, "Efficient 4-bit Embedding Operation Implementation", Table 1):
+// for every bag, gather the rows its indices name from a row-wise 4-bit table, de-quantize them
+// (x_float = scale * x_int + bias) and add them up.
+//
+// Bound by HBM gathers: d/2 bytes of codes plus two binary16 parameters per looked-up row, at
+// random rows.  One thread owns 8 consecutive elements of one bag (one 32-bit word of every row it
+// gathers) and accumulates them left to right in binary32, so the result does not depend on the
+// launch shape.  The index stream of a bag is read four at a time so that four row gathers are in
+// flight per thread; the accumulation order stays the index order.  Indices outside [0, rows) add
+// nothing; offsets are clamped to [0, n_indices], so no input can cause an out-of-range read.
+#include "e4q_device.h"
+#include "e4q_launch.h"
+
+namespace e4q {
+
+constexpr int kSlsBlock = 256;
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ void sls_add_word(float (&acc)[8], uint32_t c, float s, float b)
+{
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = acc[e] + __builtin_fmaf((float)((c >> (4 * e)) & 15u), s, b);
+}
+
+struct SlsRow {
+    uint32_t c;
+    float s, b;
+};
+
+// Gathers word `word` of row r (all zero, which adds +0, when r is out of range).
+template <typename Tidx>
+__device__ __forceinline__ SlsRow sls_gather(const uint32_t* __restrict__ codes, const uint16_t* __restrict__ sc,
+                                             const uint16_t* __restrict__ bi, int64_t rows, uint32_t wpr,
+                                             uint32_t word, Tidx idx)
+{
+    const int64_t r = (int64_t)idx;
+    const bool ok = r >= 0 && r < rows;
+    const int64_t rr = ok ? r : 0;
+    SlsRow g;
+    g.c = ok ? codes[rr * wpr + word] : 0u;
+    g.s = ok ? f16_bits_to_float(sc[rr]) : 0.0f;
+    g.b = ok ? f16_bits_to_float(bi[rr]) : 0.0f;
+    return g;
+}
+
+// dim % 8 == 0, codes 4-byte aligned, out 16-byte aligned.
+template <typename Tidx>
+__global__ void __launch_bounds__(kSlsBlock) sls_w8_kernel(const uint32_t* __restrict__ codes,
+                                                           const uint16_t* __restrict__ sc,
+                                                           const uint16_t* __restrict__ bi, int64_t rows,
+                                                           uint32_t wpr, const Tidx* __restrict__ indices,
+                                                           int64_t n_indices, const int64_t* __restrict__ offsets,
+                                                           int64_t n_bags, floatx4* __restrict__ out)
+{
+    const int64_t t = (int64_t)blockIdx.x * kSlsBlock + threadIdx.x;
+    const int64_t bag = (n_bags * wpr <= 0xffffffffLL) ? (int64_t)((uint32_t)t / wpr) : t / wpr;
+    if (bag >= n_bags) return;
+    const uint32_t word = (uint32_t)(t - bag * wpr);
+    const int64_t lo = offsets[bag], hi = offsets[bag + 1];
+    const int64_t begin = lo < 0 ? 0 : (lo > n_indices ? n_indices : lo);
+    const int64_t end = hi < begin ? begin : (hi > n_indices ? n_indices : hi);
+
+    float acc[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+    int64_t i = begin;
+    for (; i + 4 <= end; i += 4) {
+        const Tidx i0 = indices[i], i1 = indices[i + 1], i2 = indices[i + 2], i3 = indices[i + 3];
+        const SlsRow g0 = sls_gather(codes, sc, bi, rows, wpr, word, i0);
+        const SlsRow g1 = sls_gather(codes, sc, bi, rows, wpr, word, i1);
+        const SlsRow g2 = sls_gather(codes, sc, bi, rows, wpr, word, i2);
+        const SlsRow g3 = sls_gather(codes, sc, bi, rows, wpr, word, i3);
+        sls_add_word(acc, g0.c, g0.s, g0.b);
+        sls_add_word(acc, g1.c, g1.s, g1.b);
+        sls_add_word(acc, g2.c, g2.s, g2.b);
+        sls_add_word(acc, g3.c, g3.s, g3.b);
+    }
+    for (; i < end; ++i) {
+        const SlsRow g = sls_gather(codes, sc, bi, rows, wpr, word, indices[i]);
+        sls_add_word(acc, g.c, g.s, g.b);
+    }
+    floatx4 v0 = {acc[0], acc[1], acc[2], acc[3]}, v1 = {acc[4], acc[5], acc[6], acc[7]};
+    out[2 * t] = v0;
+    out[2 * t + 1] = v1;
+}
+
+// Any dim and alignment: one thread per output element.
+template <typename Tidx>
+__global__ void __launch_bounds__(kSlsBlock) sls_any_kernel(const uint8_t* __restrict__ codes,
+                                                            const uint16_t* __restrict__ sc,
+                                                            const uint16_t* __restrict__ bi, int64_t rows,
+                                                            uint32_t dim, const Tidx* __restrict__ indices,
+                                                            int64_t n_indices, const int64_t* __restrict__ offsets,
+                                                            int64_t n_bags, float* __restrict__ out)
+{
+    const int64_t t = (int64_t)blockIdx.x * kSlsBlock + threadIdx.x;
+    const int64_t bag = t / dim;
+    if (bag >= n_bags) return;
+    const uint32_t k = (uint32_t)(t - bag * dim);
+    const uint32_t nbytes = (dim + 1) / 2;
+    const int64_t lo = offsets[bag], hi = offsets[bag + 1];
+    const int64_t begin = lo < 0 ? 0 : (lo > n_indices ? n_indices : lo);
+    const int64_t end = hi < begin ? begin : (hi > n_indices ? n_indices : hi);
+    float acc = 0.0f;
+    for (int64_t i = begin; i < end; ++i) {
+        const int64_t r = (int64_t)indices[i];
+        if (r < 0 || r >= rows) continue;
+        const uint32_t byte = codes[r * nbytes + k / 2];
+        const uint32_t q = (k & 1u) ? (byte >> 4) : (byte & 15u);
+        acc = acc + __builtin_fmaf((float)q, f16_bits_to_float(sc[r]), f16_bits_to_float(bi[r]));
+    }
+    out[t] = acc;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Fused records: [codes | pad to even | scale f16 | bias f16 | pad] every `row_pitch` bytes, so
+// that one lookup touches one place in memory instead of three (the separate scale and bias
+// arrays cost a 128-byte line each per lookup).
+// ---------------------------------------------------------------------------------------------
+
+// Any shape: one thread per byte of the records.
+__global__ void __launch_bounds__(kSlsBlock) fuse_rows_any_kernel(const uint8_t* __restrict__ codes,
+                                                                  const uint16_t* __restrict__ sc,
+                                                                  const uint16_t* __restrict__ bi, int64_t rows,
+                                                                  uint32_t nbytes, uint32_t pitch,
+                                                                  uint8_t* __restrict__ fused)
+{
+    const int64_t t = (int64_t)blockIdx.x * kSlsBlock + threadIdx.x;
+    const int64_t r = t / pitch;
+    if (r >= rows) return;
+    const uint32_t k = (uint32_t)(t - r * pitch);
+    const uint32_t params_at = (nbytes + 1u) & ~1u;
+    uint8_t v = 0;
+    if (k < nbytes) v = codes[r * nbytes + k];
+    else if (k >= params_at && k < params_at + 2) v = (uint8_t)(sc[r] >> (8 * (k - params_at)));
+    else if (k >= params_at + 2 && k < params_at + 4) v = (uint8_t)(bi[r] >> (8 * (k - params_at - 2)));
+    fused[t] = v;
+}
+
+// nbytes % 4 == 0, pitch % 4 == 0, 4-byte aligned buffers: one thread per 32-bit word.
+__global__ void __launch_bounds__(kSlsBlock) fuse_rows_w_kernel(const uint32_t* __restrict__ codes,
+                                                                const uint16_t* __restrict__ sc,
+                                                                const uint16_t* __restrict__ bi, int64_t rows,
+                                                                uint32_t wpr, uint32_t pitch_words,
+                                                                uint32_t* __restrict__ fused)
+{
+    const int64_t t = (int64_t)blockIdx.x * kSlsBlock + threadIdx.x;
+    const int64_t r = t / pitch_words;
+    if (r >= rows) return;
+    const uint32_t k = (uint32_t)(t - r * pitch_words);
+    uint32_t v = 0;
+    if (k < wpr) v = codes[r * wpr + k];
+    else if (k == wpr) v = (uint32_t)sc[r] | ((uint32_t)bi[r] << 16);
+    fused[t] = v;
+}
+
+hipError_t launch_fuse_rows(const uint8_t* codes, const uint16_t* sc, const uint16_t* bi, int64_t rows,
+                            int32_t dim, int64_t row_pitch, uint8_t* fused, hipStream_t stream)
+{
+    const uint32_t nbytes = (uint32_t)((dim + 1) / 2);
+    const bool words = nbytes % 4 == 0 && row_pitch % 4 == 0 && reinterpret_cast<uintptr_t>(codes) % 4 == 0 &&
+                       reinterpret_cast<uintptr_t>(fused) % 4 == 0;
+    const int64_t threads = words ? rows * (row_pitch / 4) : rows * row_pitch;
+    const int64_t blocks = (threads + kSlsBlock - 1) / kSlsBlock;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (words)
+        hipLaunchKernelGGL(fuse_rows_w_kernel, dim3((unsigned)blocks), dim3(kSlsBlock), 0, stream,
+                           reinterpret_cast<const uint32_t*>(codes), sc, bi, rows, nbytes / 4,
+                           (uint32_t)(row_pitch / 4), reinterpret_cast<uint32_t*>(fused));
+    else
+        hipLaunchKernelGGL(fuse_rows_any_kernel, dim3((unsigned)blocks), dim3(kSlsBlock), 0, stream, codes, sc, bi,
+                           rows, nbytes, (uint32_t)row_pitch, fused);
+    return hipGetLastError();
+}
+
+// Lookup over fused records; dim % 8 == 0, pitch % 4 == 0, 4-byte aligned records, 16-byte aligned out.
+// One thread owns WPT consecutive code words (8 * WPT elements) of one bag.
+template <typename Tidx, int WPT>
+__global__ void __launch_bounds__(kSlsBlock) sls_fused_w8_kernel(const uint32_t* __restrict__ fused, int64_t rows,
+                                                                 uint32_t wpr, uint32_t pitch_words,
+                                                                 const Tidx* __restrict__ indices, int64_t n_indices,
+                                                                 const int64_t* __restrict__ offsets, int64_t n_bags,
+                                                                 floatx4* __restrict__ out)
+{
+    typedef uint32_t words_t __attribute__((ext_vector_type(WPT), aligned(4)));
+    const uint32_t tpb = wpr / WPT;  // threads per bag
+    const int64_t t = (int64_t)blockIdx.x * kSlsBlock + threadIdx.x;
+    const int64_t bag = (n_bags * tpb <= 0xffffffffLL) ? (int64_t)((uint32_t)t / tpb) : t / tpb;
+    if (bag >= n_bags) return;
+    const uint32_t word = (uint32_t)(t - bag * tpb) * WPT;
+    const int64_t lo = offsets[bag], hi = offsets[bag + 1];
+    const int64_t begin = lo < 0 ? 0 : (lo > n_indices ? n_indices : lo);
+    const int64_t end = hi < begin ? begin : (hi > n_indices ? n_indices : hi);
+
+    struct Rec {
+        uint32_t c[WPT];
+        float s, b;
+    };
+    auto gather = [&](Tidx idx) {
+        const int64_t r = (int64_t)idx;
+        const bool ok = r >= 0 && r < rows;
+        const uint32_t* rec = fused + (ok ? r : 0) * pitch_words;
+        Rec g;
+        const uint32_t sb = ok ? rec[wpr] : 0u;  // scale and bias 0: the row adds +0
+        if constexpr (WPT == 1) {
+            g.c[0] = rec[word];
+        } else {
+            const words_t v = *reinterpret_cast<const words_t*>(rec + word);
+#pragma unroll
+            for (int w = 0; w < WPT; ++w) g.c[w] = v[w];
+        }
+        g.s = f16_bits_to_float((uint16_t)(sb & 0xffffu));
+        g.b = f16_bits_to_float((uint16_t)(sb >> 16));
+        return g;
+    };
+    float acc[WPT][8];
+#pragma unroll
+    for (int w = 0; w < WPT; ++w)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[w][e] = 0.0f;
+    auto add = [&](const Rec& g) {
+#pragma unroll
+        for (int w = 0; w < WPT; ++w) sls_add_word(acc[w], g.c[w], g.s, g.b);
+    };
+
+    int64_t i = begin;
+    for (; i + 4 <= end; i += 4) {
+        const Tidx i0 = indices[i], i1 = indices[i + 1], i2 = indices[i + 2], i3 = indices[i + 3];
+        const Rec g0 = gather(i0), g1 = gather(i1), g2 = gather(i2), g3 = gather(i3);
+        add(g0);
+        add(g1);
+        add(g2);
+        add(g3);
+    }
+    for (; i < end; ++i) add(gather(indices[i]));
+    floatx4* o = out + 2 * (bag * wpr + word);
+#pragma unroll
+    for (int w = 0; w < WPT; ++w) {
+        floatx4 v0 = {acc[w][0], acc[w][1], acc[w][2], acc[w][3]}, v1 = {acc[w][4], acc[w][5], acc[w][6], acc[w][7]};
+        o[2 * w] = v0;
+        o[2 * w + 1] = v1;
+    }
+}
+
+// Lookup over fused records, any dim / pitch / alignment: one thread per output element.
+template <typename Tidx>
+__global__ void __launch_bounds__(kSlsBlock) sls_fused_any_kernel(const uint8_t* __restrict__ fused, int64_t rows,
+                                                                  uint32_t dim, int64_t pitch,
+                                                                  const Tidx* __restrict__ indices, int64_t n_indices,
+                                                                  const int64_t* __restrict__ offsets, int64_t n_bags,
+                                                                  float* __restrict__ out)
+{
+    const int64_t t = (int64_t)blockIdx.x * kSlsBlock + threadIdx.x;
+    const int64_t bag = t / dim;
+    if (bag >= n_bags) return;
+    const uint32_t k = (uint32_t)(t - bag * dim);
+    const uint32_t params_at = (((dim + 1) / 2) + 1u) & ~1u;
+    const int64_t lo = offsets[bag], hi = offsets[bag + 1];
+    const int64_t begin = lo < 0 ? 0 : (lo > n_indices ? n_indices : lo);
+    const int64_t end = hi < begin ? begin : (hi > n_indices ? n_indices : hi);
+    float acc = 0.0f;
+    for (int64_t i = begin; i < end; ++i) {
+        const int64_t r = (int64_t)indices[i];
+        if (r < 0 || r >= rows) continue;
+        const uint8_t* rec = fused + r * pitch;
+        const uint32_t byte = rec[k / 2];
+        const uint32_t q = (k & 1u) ? (byte >> 4) : (byte & 15u);
+        const uint16_t sbits = (uint16_t)(rec[params_at] | (rec[params_at + 1] << 8));
+        const uint16_t bbits = (uint16_t)(rec[params_at + 2] | (rec[params_at + 3] << 8));
+        acc = acc + __builtin_fmaf((float)q, f16_bits_to_float(sbits), f16_bits_to_float(bbits));
+    }
+    out[t] = acc;
+}
+
+template <typename Tidx>
+static hipError_t launch_sls_fused_t(const uint8_t* fused, int64_t rows, int32_t dim, int64_t pitch,
+                                     const void* indices, int64_t n_indices, const int64_t* offsets, int64_t n_bags,
+                                     float* out, hipStream_t stream)
+{
+    const bool fast = dim % 8 == 0 && pitch % 4 == 0 && reinterpret_cast<uintptr_t>(fused) % 4 == 0 &&
+                      reinterpret_cast<uintptr_t>(out) % 16 == 0;
+    const int wpr = dim / 8;
+    int wpt = 1;
+    if (fast) {
+        wpt = wpr % 2 == 0 ? 2 : 1;  // 8-byte gathers measured 6 % faster than 4-byte ones, 16-byte ones no better
+    }
+    const int64_t threads = fast ? n_bags * (wpr / wpt) : n_bags * dim;
+    const int64_t blocks = (threads + kSlsBlock - 1) / kSlsBlock;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)blocks), block(kSlsBlock);
+    const uint32_t* f32 = reinterpret_cast<const uint32_t*>(fused);
+    const Tidx* idx = static_cast<const Tidx*>(indices);
+    floatx4* o4 = reinterpret_cast<floatx4*>(out);
+    if (!fast)
+        hipLaunchKernelGGL(sls_fused_any_kernel<Tidx>, grid, block, 0, stream, fused, rows, (uint32_t)dim, pitch, idx,
+                           n_indices, offsets, n_bags, out);
+    else if (wpt == 2)
+        hipLaunchKernelGGL((sls_fused_w8_kernel<Tidx, 2>), grid, block, 0, stream, f32, rows, (uint32_t)wpr,
+                           (uint32_t)(pitch / 4), idx, n_indices, offsets, n_bags, o4);
+    else
+        hipLaunchKernelGGL((sls_fused_w8_kernel<Tidx, 1>), grid, block, 0, stream, f32, rows, (uint32_t)wpr,
+                           (uint32_t)(pitch / 4), idx, n_indices, offsets, n_bags, o4);
+    return hipGetLastError();
+}
+
+hipError_t launch_sparse_lengths_sum_fused(const uint8_t* fused, int64_t rows, int32_t dim, int64_t pitch,
+                                           const void* indices, int32_t index_bytes, int64_t n_indices,
+                                           const int64_t* offsets, int64_t n_bags, float* out, hipStream_t stream)
+{
+    return index_bytes == 4
+               ? launch_sls_fused_t<int32_t>(fused, rows, dim, pitch, indices, n_indices, offsets, n_bags, out, stream)
+               : launch_sls_fused_t<int64_t>(fused, rows, dim, pitch, indices, n_indices, offsets, n_bags, out, stream);
+}
+
+template <typename Tidx>
+static hipError_t launch_sls_t(const uint8_t* codes, const uint16_t* sc, const uint16_t* bi, int64_t rows,
+                               int32_t dim, const void* indices, int64_t n_indices, const int64_t* offsets,
+                               int64_t n_bags, float* out, hipStream_t stream)
+{
+    const bool fast = dim % 8 == 0 && reinterpret_cast<uintptr_t>(codes) % 4 == 0 &&
+                      reinterpret_cast<uintptr_t>(out) % 16 == 0;
+    const int64_t threads = fast ? n_bags * (dim / 8) : n_bags * dim;
+    const int64_t blocks = (threads + kSlsBlock - 1) / kSlsBlock;
+    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (fast)
+        hipLaunchKernelGGL(sls_w8_kernel<Tidx>, dim3((unsigned)blocks), dim3(kSlsBlock), 0, stream,
+                           reinterpret_cast<const uint32_t*>(codes), sc, bi, rows, (uint32_t)(dim / 8),
+                           static_cast<const Tidx*>(indices), n_indices, offsets, n_bags,
+                           reinterpret_cast<floatx4*>(out));
+    else
+        hipLaunchKernelGGL(sls_any_kernel<Tidx>, dim3((unsigned)blocks), dim3(kSlsBlock), 0, stream, codes, sc, bi,
+                           rows, (uint32_t)dim, static_cast<const Tidx*>(indices), n_indices, offsets, n_bags, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_sparse_lengths_sum(const uint8_t* codes, const uint16_t* sc, const uint16_t* bi, int64_t rows,
+                                     int32_t dim, const void* indices, int32_t index_bytes, int64_t n_indices,
+                                     const int64_t* offsets, int64_t n_bags, float* out, hipStream_t stream)
+{
+    return index_bytes == 4
+               ? launch_sls_t<int32_t>(codes, sc, bi, rows, dim, indices, n_indices, offsets, n_bags, out, stream)
+               : launch_sls_t<int64_t>(codes, sc, bi, rows, dim, indices, n_indices, offsets, n_bags, out, stream);
+}
+
+}  // namespace e4q

@@ -126,3 +126,17 @@ def mixture_table(rows: int = 2_000_000, dim: int = 64, seed: int = BASE_SEED + 
         comp = torch.randint(0, n_comp, (n, dim), generator=g, device=device)
         out[r0:r1] = torch.gather(means, 1, comp) + torch.randn((n, dim), generator=g, device=device) * sigma
     return out
+
+
+def lookup_bags(rows: int, n_bags: int = 1 << 20, min_len: int = 1, max_len: int = 64, seed: int = BASE_SEED + 5,
+                device="cpu", index_dtype=torch.int64):
+    """Index stream of a pooled embedding lookup: bag lengths uniform in [min_len, max_len], row
+    numbers uniform over the table (no locality: the cache non-resident case of the paper's
+    Table 1).  Returns (indices [sum of lengths], offsets int64 [n_bags + 1])."""
+    g = _gen(device, seed)
+    lengths = torch.randint(min_len, max_len + 1, (n_bags,), generator=g, device=device)
+    offsets = torch.zeros(n_bags + 1, dtype=torch.int64, device=device)
+    offsets[1:] = torch.cumsum(lengths, 0)
+    total = int(offsets[-1])
+    indices = torch.randint(0, rows, (total,), generator=g, device=device).to(index_dtype)
+    return indices, offsets

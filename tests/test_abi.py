@@ -31,7 +31,8 @@ def test_header_declares_the_expected_entry_points():
     names = declared_functions()
     for must in ["e4q_quantize_rowwise_greedy", "e4q_dequantize", "e4q_quantize_rowwise_greedy_batch",
                  "e4q_greedy_iterations", "e4q_strerror", "e4q_last_hip_error", "e4q_version",
-                 "e4q_quantize_rowwise_kmeans16", "e4q_dequantize_codebook"]:
+                 "e4q_quantize_rowwise_kmeans16", "e4q_dequantize_codebook", "e4q_sparse_lengths_sum", "e4q_fuse_rows",
+                 "e4q_sparse_lengths_sum_fused", "e4q_fused_row_bytes"]:
         assert must in names
 
 
@@ -115,6 +116,32 @@ def test_validation_rejects_bad_arguments_before_any_launch(lib):
     assert dc(p, p, -1, 64, p, None) == -2
     assert dc(p, None, 10, 64, p, None) == -1
     assert dc(None, None, 0, 64, None, None) == 0
+
+    sls = lib.e4q_sparse_lengths_sum
+    p8 = ctypes.c_void_p(0x1000)
+    assert sls(p, p, p, 10, 64, 8, p8, 8, 5, p8, 2, p, None) == -3
+    assert sls(p, p, p, 10, 64, 4, p8, 2, 5, p8, 2, p, None) == -5
+    assert sls(p, p, p, 10, 0, 4, p8, 8, 5, p8, 2, p, None) == -2
+    assert sls(p, p, p, 10, 64, 4, p8, 8, -1, p8, 2, p, None) == -2
+    assert sls(p, p, p, 10, 64, 4, None, 8, 5, p8, 2, p, None) == -1
+    assert sls(p, p, p, 10, 64, 4, p8, 8, 5, None, 2, p, None) == -1
+    assert sls(p, p, p, 10, 64, 4, p8, 8, 5, ctypes.c_void_p(0x1004), 2, p, None) == -7
+    assert sls(None, None, None, 0, 64, 4, None, 8, 0, None, 0, None, None) == 0
+
+    lib.e4q_fused_row_bytes.restype = ctypes.c_int64
+    assert lib.e4q_fused_row_bytes(128) == 68 and lib.e4q_fused_row_bytes(64) == 36 and lib.e4q_fused_row_bytes(8) == 8
+    assert lib.e4q_fused_row_bytes(5) == 8 and lib.e4q_fused_row_bytes(6) == 8 and lib.e4q_fused_row_bytes(0) == -2
+    fr = lib.e4q_fuse_rows
+    assert fr(p, p, p, 10, 128, 4, 66, p, None) == -2      # smaller than the record
+    assert fr(p, p, p, 10, 128, 4, 69, p, None) == -2      # odd
+    assert fr(p, p, p, 10, 128, 8, 68, p, None) == -3
+    assert fr(p, p, p, 10, 128, 4, 68, None, None) == -1
+    assert fr(None, None, None, 0, 128, 4, 68, None, None) == 0
+    sf = lib.e4q_sparse_lengths_sum_fused
+    assert sf(p, 10, 128, 4, 66, p8, 8, 5, p8, 2, p, None) == -2
+    assert sf(p, 10, 128, 4, 68, p8, 3, 5, p8, 2, p, None) == -5
+    assert sf(None, 10, 128, 4, 68, p8, 8, 5, p8, 2, p, None) == -1
+    assert sf(None, 0, 128, 4, 68, None, 8, 0, None, 0, None, None) == 0
 
     from paper_1911_02079_amd.binding import TableDesc
 

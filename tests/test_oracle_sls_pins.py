@@ -91,3 +91,24 @@ def test_empty_inputs(oracle_lib):
     assert out.shape == (0, 8)
     out = oracle_lib.sparse_lengths_sum(codes, sc, bi, 8, np.zeros(0, np.int64), np.zeros(5, np.int64))
     assert out.shape == (4, 8) and np.all(out == 0)
+
+
+def test_fused_records_hold_codes_then_scale_then_bias(oracle_lib):
+    """The fused lookup record, byte by byte, on a hand-written example (little-endian binary16)."""
+    codes = np.array([[0x10, 0x32, 0x54], [0xAB, 0xCD, 0xEF]], dtype=np.uint8)   # dim 5 or 6: 3 code bytes
+    sc, bi = f16([1.0, 0.5]), f16([-2.0, 3.0])        # 0x3C00, 0x3800 / 0xC000, 0x4200
+    got = oracle_lib.fuse_rows(codes, sc, bi, 6, 10)
+    assert got.tolist() == [[0x10, 0x32, 0x54, 0, 0x00, 0x3C, 0x00, 0xC0, 0, 0],
+                            [0xAB, 0xCD, 0xEF, 0, 0x00, 0x38, 0x00, 0x42, 0, 0]]
+    with pytest.raises(ValueError):
+        oracle_lib.fuse_rows(codes, sc, bi, 6, 7)      # too small
+    with pytest.raises(ValueError):
+        oracle_lib.fuse_rows(codes, sc, bi, 6, 9)      # odd
+    # and the codes / parameters can be read back from where the layout says they are
+    rng = np.random.default_rng(0)
+    c = rng.integers(0, 256, (50, 32)).astype(np.uint8)
+    s, b = rng.integers(0, 0x7BFF, 50).astype(np.uint16), rng.integers(0, 0x7BFF, 50).astype(np.uint16)
+    rec = oracle_lib.fuse_rows(c, s, b, 64, 68)
+    assert np.array_equal(rec[:, :32], c)
+    assert np.array_equal(rec[:, 32:34].copy().view(np.uint16)[:, 0], s)
+    assert np.array_equal(rec[:, 34:36].copy().view(np.uint16)[:, 0], b)

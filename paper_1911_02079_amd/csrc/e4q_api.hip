@@ -2,9 +2,11 @@
 // Host code only: argument validation, choice of kernel, launch on the caller's stream.
 #include "../../include/e4q.h"
 
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <vector>
 
 #include "e4q_launch.h"
 
@@ -128,11 +130,64 @@ int e4q_quantize_rowwise_greedy_batch(const e4q_table_desc* descs, int32_t n_tab
         if (rc != E4Q_OK) return rc;
     }
     const int32_t n_iter = e4q_greedy_iterations(n_bins, ratio);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    try {  // the bookkeeping below allocates host memory; nothing may be thrown across the C boundary
+    std::vector<char> done((size_t)n_tables, 0);
+    // Tables that share a dimension and an input type, and together have enough rows for the
+    // one-row-per-lane kernels, go out in grouped launches of up to kMaxGroupTables tables.
+    if (n_iter > 0) {
+        for (int32_t t = 0; t < n_tables; ++t) {
+            if (done[t] || descs[t].rows == 0 || !e4q::rpl_supports_dim(descs[t].dim)) continue;
+            std::vector<int32_t> members;
+            int64_t waves = 0;
+            for (int32_t u = t; u < n_tables; ++u)
+                if (!done[u] && descs[u].rows > 0 && descs[u].dim == descs[t].dim && descs[u].dtype == descs[t].dtype) {
+                    members.push_back(u);
+                    waves += (descs[u].rows + 63) / 64;
+                }
+            if (members.size() < 2 || waves < 512 || waves > 0x7fffffffLL) continue;
+            for (size_t first = 0; first < members.size(); first += e4q::kMaxGroupTables) {
+                e4q::GreedyGroup g;
+                g.n_tables = (int32_t)std::min<size_t>(e4q::kMaxGroupTables, members.size() - first);
+                g.n_iter = n_iter;
+                g.n_bins = (float)n_bins;
+                uint32_t blocks = 0;
+                for (int32_t k = 0; k < e4q::kMaxGroupTables; ++k) {
+                    if (k < g.n_tables) {
+                        const e4q_table_desc& d = descs[members[first + k]];
+                        const size_t esz = d.dtype == E4Q_F32 ? 4 : 2;
+                        e4q::GreedyTable& e = g.tables[k];
+                        e.table = d.table;
+                        e.rows = d.rows;
+                        e.row_stride = d.row_stride;
+                        e.codes = d.codes;
+                        e.scale_f16 = d.scale_f16;
+                        e.bias_f16 = d.bias_f16;
+                        e.vec_loads = (aligned(d.table, 16) && (d.row_stride * esz) % 16 == 0) ? 1u : 0u;
+                        e.vec_stores = aligned(d.codes, 16) ? 2u : (aligned(d.codes, 4) ? 1u : 0u);
+                        blocks += (uint32_t)((d.rows + 63) / 64);
+                        done[members[first + k]] = 1;
+                    } else {
+                        g.tables[k] = e4q::GreedyTable{};
+                    }
+                    g.block_end[k] = blocks;
+                }
+                const hipError_t err = descs[t].dtype == E4Q_F32 ? e4q::launch_greedy_rpl_group_f32(g, descs[t].dim, stream)
+                                                                 : e4q::launch_greedy_rpl_group_f16(g, descs[t].dim, stream);
+                if (err != hipSuccess) return fail_launch(err);
+            }
+        }
+    }
     for (int32_t t = 0; t < n_tables; ++t) {
+        if (done[t]) continue;
         const e4q_table_desc& d = descs[t];
         rc = enqueue_greedy(d.table, d.dtype, d.rows, d.dim, d.row_stride, n_bins, n_iter, d.codes,
-                            d.scale_f16, d.bias_f16, static_cast<hipStream_t>(hip_stream));
+                            d.scale_f16, d.bias_f16, stream);
         if (rc != E4Q_OK) return rc;
+    }
+    } catch (...) {
+        std::snprintf(g_hip_error, sizeof(g_hip_error), "host memory allocation failed");
+        return E4Q_ERR_LAUNCH;
     }
     return E4Q_OK;
 }

@@ -20,12 +20,34 @@ struct GreedyArgs {
     uint32_t vec_stores;  // 0: byte stores, 1: codes base 4-byte aligned, 2: 16-byte aligned
 };
 
+// One launch over several tables of the same dimension and input type (one row per lane).
+constexpr int kMaxGroupTables = 16;
+struct GreedyTable {
+    const void* table;
+    int64_t rows;
+    int64_t row_stride;
+    uint8_t* codes;
+    uint16_t* scale_f16;
+    uint16_t* bias_f16;
+    uint32_t vec_loads;
+    uint32_t vec_stores;
+};
+struct GreedyGroup {
+    int32_t n_tables;  // 1 .. kMaxGroupTables
+    int32_t n_iter;
+    float n_bins;
+    uint32_t block_end[kMaxGroupTables];  // running total of ceil(rows / 64) workgroups
+    GreedyTable tables[kMaxGroupTables];
+};
+
 // Register-resident kernels exist for these dimensions (multiples of 8 up to 128).
 inline bool rpl_supports_dim(int32_t dim) { return dim >= 8 && dim <= 128 && dim % 8 == 0; }
 
 // Each returns hipGetLastError() after enqueueing.
 hipError_t launch_greedy_rpl_f32(const GreedyArgs& a, int32_t dim, hipStream_t stream);
 hipError_t launch_greedy_rpl_f16(const GreedyArgs& a, int32_t dim, hipStream_t stream);
+hipError_t launch_greedy_rpl_group_f32(const GreedyGroup& g, int32_t dim, hipStream_t stream);
+hipError_t launch_greedy_rpl_group_f16(const GreedyGroup& g, int32_t dim, hipStream_t stream);
 // Sub-wave layouts: L lanes per row, E contiguous elements per lane (see greedy_swl.h).
 // "small": E in {8, 16, 32, 64}; "big": E = 128.  Needs dim <= E * L.
 hipError_t launch_greedy_swl_f32_small(const GreedyArgs& a, int32_t dim, int E, int L, hipStream_t stream);

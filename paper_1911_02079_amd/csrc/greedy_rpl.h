@@ -70,10 +70,10 @@ __device__ __forceinline__ float range_loss(const float (&x)[D], float lo, float
     return tree_sum<0, next_pow2(D), D>([&](auto k) { return elem_sq_err(x[decltype(k)::value], p); });
 }
 
+// The whole path for the row this lane owns: load, min/max, Algorithm 1, encode, store.
 template <int D, typename Tin>
-__global__ void __launch_bounds__(kRplBlock) greedy_rpl_kernel(GreedyArgs a)
+__device__ __forceinline__ void greedy_rpl_row(const GreedyArgs& a, int64_t row)
 {
-    const int64_t row = (int64_t)blockIdx.x * kRplBlock + threadIdx.x;
     const bool live = row < a.rows;
     const int64_t r = live ? row : a.rows - 1;  // tail lanes redo the last row and store nothing
 
@@ -148,6 +148,44 @@ __global__ void __launch_bounds__(kRplBlock) greedy_rpl_kernel(GreedyArgs a)
 #pragma unroll
         for (int b = 0; b < NBYTES; ++b) out[b] = (uint8_t)(w[b / 4] >> (8 * (b % 4)));
     }
+}
+
+template <int D, typename Tin>
+__global__ void __launch_bounds__(kRplBlock) greedy_rpl_kernel(GreedyArgs a)
+{
+    greedy_rpl_row<D, Tin>(a, (int64_t)blockIdx.x * kRplBlock + threadIdx.x);
+}
+
+// Several tables of one dimension and input type in one launch: workgroup b belongs to the first
+// table whose block_end exceeds b.  Small tables then share the chip with large ones instead of
+// each waiting for a launch of its own to drain.
+template <int D, typename Tin>
+__global__ void __launch_bounds__(kRplBlock) greedy_rpl_group_kernel(GreedyGroup g)
+{
+    int t = 0;
+    while (t + 1 < g.n_tables && blockIdx.x >= g.block_end[t]) ++t;  // uniform: at most 15 scalar steps
+    const uint32_t first_block = t == 0 ? 0u : g.block_end[t - 1];
+    const GreedyTable& e = g.tables[t];
+    GreedyArgs a;
+    a.table = e.table;
+    a.rows = e.rows;
+    a.row_stride = e.row_stride;
+    a.n_iter = g.n_iter;
+    a.n_bins = g.n_bins;
+    a.codes = e.codes;
+    a.scale_f16 = e.scale_f16;
+    a.bias_f16 = e.bias_f16;
+    a.vec_loads = e.vec_loads;
+    a.vec_stores = e.vec_stores;
+    greedy_rpl_row<D, Tin>(a, (int64_t)(blockIdx.x - first_block) * kRplBlock + threadIdx.x);
+}
+
+template <int D, typename Tin>
+inline hipError_t launch_greedy_rpl_group(const GreedyGroup& g, hipStream_t stream)
+{
+    const uint32_t blocks = g.block_end[g.n_tables - 1];
+    hipLaunchKernelGGL((greedy_rpl_group_kernel<D, Tin>), dim3(blocks), dim3(kRplBlock), 0, stream, g);
+    return hipGetLastError();
 }
 
 // Host-side launcher for one (D, Tin) instantiation.

@@ -6,4 +6,8 @@ hipError_t launch_greedy_rpl_f16(const GreedyArgs& a, int32_t dim, hipStream_t s
 {
     return dispatch_greedy_rpl<_Float16>(a, dim, stream);
 }
+hipError_t launch_greedy_rpl_group_f16(const GreedyGroup& g, int32_t dim, hipStream_t stream)
+{
+    return dispatch_greedy_rpl_group<_Float16>(g, dim, stream);
+}
 }  // namespace e4q

@@ -101,6 +101,32 @@ def test_config4_batch_of_half_tables(e4q, oracle_lib):
         assert np.array_equal(bias.cpu().view(torch.int16).numpy().view(np.uint16), o_bias), f"table {k}"
 
 
+def test_batch_grouping(e4q, oracle_lib):
+    """More tables of one dimension than fit one grouped launch (16), mixed with other dimensions,
+    input types, an empty table and a table too odd to group."""
+    from paper_1911_02079_amd import synth
+
+    rng = np.random.default_rng(0)
+    tables = []
+    for k in range(40):
+        tables.append(synth.gaussian_table(int(rng.integers(100, 3000)), 64, 0.1, seed=9000 + k, device="cuda"))
+    for k in range(5):
+        tables.append(synth.gaussian_table(int(rng.integers(5000, 30000)), 32, 0.1, seed=9100 + k, device="cuda",
+                                           dtype=torch.float16))
+    tables.append(torch.empty((0, 64), device="cuda"))
+    tables.append(synth.gaussian_table(777, 100, 0.1, seed=9200, device="cuda"))
+    tables.append(synth.gaussian_table(50, 128, 0.1, seed=9201, device="cuda"))
+    say(f"batch grouping: {len(tables)} tables")
+    outs = e4q.quantize_rowwise_greedy_batch(tables, 200, 0.16)
+    torch.cuda.synchronize()
+    for k, (t, (codes, scale, bias)) in enumerate(zip(tables, outs)):
+        if t.shape[0] == 0:
+            continue
+        o = oracle_lib.quantize_rowwise_greedy(t.cpu().numpy(), 200, 0.16)
+        assert np.array_equal(codes.cpu().numpy(), o[0]), f"table {k}"
+        assert np.array_equal(f16_bits(scale), o[1]) and np.array_equal(f16_bits(bias), o[2]), f"table {k}"
+
+
 # --------------------------------------------------------------------------------------------
 # Every kernel layout.  The library picks by (rows, dim, ratio): one row per lane for many rows and
 # dim in 8, 16, ..., 128; otherwise L lanes per row with E elements per lane (E = 8 for few rows,

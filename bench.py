@@ -56,10 +56,10 @@ def greedy_lane_ops_per_row(dim: int, n_iter: int) -> int:
 
 def kmeans_lane_ops_per_row(dim: int, iters: int) -> int:
     """Lane operations of the 16-means path per row: per element and Lloyd round 16 subtractions,
-    15 compares, 15 minimum updates, 15 index selects and one binary64 add (62); one more
-    assignment pass against the rounded codebook (61 per element); 16 means per round (counted as
+    8 three-input minimums, 15 compares, 15 index selects and one binary64 add (55); one more
+    assignment pass against the rounded codebook (54 per element); 16 means per round (counted as
     one operation each); 2 per element for min/max."""
-    return dim * (62 * iters + 61) + 16 * iters + 2 * dim
+    return dim * (55 * iters + 54) + 16 * iters + 2 * dim
 
 
 def read_traffic(name: str):

@@ -9,7 +9,10 @@ one pass of the whole path over the table, which is already resident in HBM: the
 load, min/max, Algorithm 1's search, encode + pack, binary16 scale/bias) followed by the
 de-quantizer.  `--workload mixture_2M_x_64_kmeans16` times the codebook variant the same way;
 `--workload lookup_10M_x_128_sls` times the 4-bit SparseLengthsSum lookup over the quantized
-table (2^20 bags of 1..64 uniformly random rows; bound by HBM gathers).
+table (2^20 bags of 1..64 uniformly random rows; bound by HBM gathers);
+`--workload batch_26_half_tables` times the batch entry point on 26 binary16 tables.  `--rows`,
+`--dim`, `--n-bins`, `--ratio`, `--half` vary the single-table workloads (for example `--ratio 0`
+is plain min/max quantization, which is bound by HBM instead of VALU issue).
 
 Prints ONE JSON line.  `value` is rows per second over whole steps; `kernels` gives each kernel's
 own average duration from HIP events recorded on the launch stream inside the timed region;
@@ -42,6 +45,7 @@ WORKLOADS = {
     "outlier_1M_x_64": ("greedy", "outlier_table", 1_000_000, 64, {"n_bins": 200, "ratio": 0.16}),
     "laplace_10M_x_128": ("greedy", "laplace_offset_table", 10_000_000, 128, {"n_bins": 200, "ratio": 0.16}),
     "mixture_2M_x_64_kmeans16": ("kmeans16", "mixture_table", 2_000_000, 64, {"lloyd_iters": 20}),
+    "batch_26_half_tables": ("greedy_batch", "batch_tables", 9_416_736, 0, {"n_bins": 100, "ratio": 0.16}),
     "lookup_10M_x_128_sls": ("sls", "laplace_offset_table", 10_000_000, 128, {"n_bags": 1 << 20, "max_len": 64}),
 }
 
@@ -201,12 +205,57 @@ def bench_sls(args, e4q, synth, torch, gen, rows, dim, params) -> int:
     return 0
 
 
+def bench_batch(args, e4q, synth, torch, params) -> int:
+    """26 binary16 tables through the batch entry point: one step = one e4q_quantize_rowwise_greedy_batch call."""
+    n_bins, ratio = args.n_bins or params["n_bins"], (args.ratio if args.ratio >= 0 else params["ratio"])
+    n_iter = e4q.greedy_iterations(n_bins, ratio)
+    specs = synth.batch_specs()
+    tables = synth.batch_tables(specs, device="cuda:0")
+    outs = [e4q.alloc_outputs(t.shape[0], t.shape[1], "cuda:0") for t in tables]
+    run = lambda: e4q.quantize_rowwise_greedy_batch(tables, n_bins, ratio, out=outs)  # noqa: E731
+    for _ in range(args.warmup):
+        run()
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        evs[k][0].record()
+        run()
+        evs[k][1].record()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms = sum(e[0].elapsed_time(e[1]) for e in evs) / args.steps
+    rows = sum(s.rows for s in specs)
+    ops = sum(greedy_lane_ops_per_row(s.dim, n_iter) * s.rows for s in specs)
+    nbytes = sum((2 * s.dim + s.dim // 2 + 4) * s.rows for s in specs)
+    result = {
+        "metric": "rows quantized/sec (greedy 4-bit)", "value": rows / (elapsed / args.steps), "unit": "rows/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": 1e3 * elapsed / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "tables": len(specs), "rows": rows, "input": "binary16",
+                   "dims": sorted({s.dim for s in specs}), "n_bins": n_bins, "ratio": ratio,
+                   "step": "quantize_rowwise_greedy_batch over all tables (grouped launches per dimension)"},
+        "kernels": {"greedy_rpl_group_kernel (all launches of a step)": {"avg_ms": ms, "rows_per_s": rows / (ms * 1e-3)}},
+        "roofline": {"kernel": "greedy_rpl_group_kernel", "bound": "alu", "achieved": ops / (ms * 1e-3) / 1e12,
+                     "peak": PEAK_LANE_OPS / 1e12, "unit": "T lane-op/s (plain fp32 VALU: 256 CU x 64 lanes x 2.4 GHz)",
+                     "frac": ops / (ms * 1e-3) / PEAK_LANE_OPS, "hbm_achieved_GBps": nbytes / (ms * 1e-3) / 1e9,
+                     "traffic": None},
+    }
+    print(json.dumps(result), flush=True)
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="laplace_10M_x_128", choices=sorted(WORKLOADS))
+    ap.add_argument("--rows", type=int, default=0, help="override the workload's row count")
+    ap.add_argument("--dim", type=int, default=0, help="override the workload's embedding dimension")
+    ap.add_argument("--n-bins", type=int, default=0, help="override b of Algorithm 1")
+    ap.add_argument("--ratio", type=float, default=-1.0, help="override r of Algorithm 1 (0 = plain min/max)")
+    ap.add_argument("--half", action="store_true", help="feed the table as binary16")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy kernel three times, so that a "
@@ -230,8 +279,18 @@ def main() -> int:
     method, gen, rows, dim, params = WORKLOADS[args.workload]
     if method == "sls":
         return bench_sls(args, e4q, synth, torch, gen, rows, dim, params)
+    if method == "greedy_batch":
+        return bench_batch(args, e4q, synth, torch, params)
+    rows, dim = args.rows or rows, args.dim or dim
+    params = dict(params)
+    if args.n_bins:
+        params["n_bins"] = args.n_bins
+    if args.ratio >= 0:
+        params["ratio"] = args.ratio
 
     table = getattr(synth, gen)(rows, dim, device="cuda:0")
+    if args.half:
+        table = table.half()
     xh = torch.empty((rows, dim), dtype=torch.float32, device=table.device)
     if method == "greedy":
         n_bins, ratio = params["n_bins"], params["ratio"]
@@ -239,7 +298,9 @@ def main() -> int:
         out = e4q.alloc_outputs(rows, dim, table.device)
         quantize = lambda: e4q.quantize_rowwise_greedy(table, n_bins, ratio, out=out)  # noqa: E731
         dequantize = lambda: e4q.dequantize(out[0], out[1], out[2], dim, out=xh)  # noqa: E731
-        q_name, dq_name = "greedy_rpl_kernel", "dequantize_w4_kernel"
+        # the library takes one row per lane when there are enough rows and dim is 8, 16, ..., 128
+        rpl = n_iter > 0 and (rows + 63) // 64 >= 512 and dim % 8 == 0 and dim <= 128
+        q_name, dq_name = ("greedy_rpl_kernel" if rpl else "greedy_swl_kernel"), "dequantize_w4_kernel"
         ops_per_row = greedy_lane_ops_per_row(dim, n_iter)
         out_bytes_per_row = (dim + 1) // 2 + 4
         config = {"n_bins": n_bins, "ratio": ratio, "candidate_ranges_per_row": 1 + 2 * n_iter, "nbits": 4,
@@ -315,7 +376,8 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": dict({"workload": args.workload, "rows": rows, "dim": dim}, **config),
+        "config": dict({"workload": args.workload, "rows": rows, "dim": dim,
+                        "input": "binary16" if args.half else "binary32"}, **config),
         "kernels": {
             q_name: {"avg_ms": q_ms, "rows_per_s": rows / (q_ms * 1e-3),
                      "algorithmic_GBps": q_bytes / (q_ms * 1e-3) / 1e9},
@@ -330,9 +392,13 @@ def main() -> int:
             "bytes_per_row": q_bytes // rows,
             "hbm_achieved_GBps": q_bytes / (q_ms * 1e-3) / 1e9,
             "hbm_frac": q_bytes / (q_ms * 1e-3) / PEAK_HBM_BYTES,
-            "traffic": read_traffic(f"{q_name}_{args.workload}_hbm_traffic.txt"),
+            "traffic": read_traffic(f"{q_name}_{args.workload}_hbm_traffic.txt")
+            if not (args.rows or args.dim or args.n_bins or args.ratio >= 0 or args.half) else None,
         },
     }
+    if method == "greedy" and n_iter == 0:  # plain min/max: one pass over the data, bound by HBM
+        result["roofline"].update({"bound": "hbm", "achieved": q_bytes / (q_ms * 1e-3) / 1e9, "peak": PEAK_HBM_BYTES / 1e9,
+                                   "unit": "GB/s", "frac": q_bytes / (q_ms * 1e-3) / PEAK_HBM_BYTES})
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(table, run_oracle)
     print(json.dumps(result), flush=True)

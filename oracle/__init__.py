@@ -53,15 +53,15 @@ def _load():
     lib.e4q_oracle_n_iter.restype = c.c_int32
     lib.e4q_oracle_quantize_rowwise_greedy.argtypes = [
         c.c_void_p, c.c_int, c.c_int64, c.c_int32, c.c_int64, c.c_int32, c.c_float, c.c_int,
-        c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p]
+        c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32]
     lib.e4q_oracle_quantize_rowwise_greedy.restype = c.c_int
-    lib.e4q_oracle_range_loss.argtypes = [c.c_void_p, c.c_int32, c.c_float, c.c_float]
+    lib.e4q_oracle_range_loss.argtypes = [c.c_void_p, c.c_int32, c.c_float, c.c_float, c.c_int32]
     lib.e4q_oracle_range_loss.restype = c.c_float
     lib.e4q_oracle_brute_force_row.argtypes = [
-        c.c_void_p, c.c_int32, c.c_int32, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p]
+        c.c_void_p, c.c_int32, c.c_int32, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p, c.c_int32]
     lib.e4q_oracle_brute_force_row.restype = c.c_int
     lib.e4q_oracle_dequantize.argtypes = [c.c_void_p, c.c_void_p, c.c_void_p, c.c_int64, c.c_int32,
-                                          c.c_void_p]
+                                          c.c_void_p, c.c_int32]
     lib.e4q_oracle_dequantize.restype = c.c_int
     lib.e4q_oracle_quantize_rowwise_kmeans16.argtypes = [
         c.c_void_p, c.c_int, c.c_int64, c.c_int32, c.c_int64, c.c_int32, c.c_void_p, c.c_void_p, c.c_void_p]
@@ -119,22 +119,28 @@ def n_iter(n_bins: int, ratio: float) -> int:
     return int(_load().e4q_oracle_n_iter(int(n_bins), float(ratio)))
 
 
+def packed_bytes(dim: int, nbits: int = 4) -> int:
+    """Bytes of one row of codes: 8/nbits codes per byte."""
+    per = 8 // nbits
+    return (dim + per - 1) // per
+
+
 def quantize_rowwise_greedy(table: np.ndarray, n_bins: int = 200, ratio: float = 0.16,
-                            literal_alg1: bool = False, return_search: bool = False):
-    """Algorithm 1 per row, then Eq. 1.  Returns (codes uint8 [rows, ceil(dim/2)],
+                            literal_alg1: bool = False, return_search: bool = False, nbits: int = 4):
+    """Algorithm 1 per row, then Eq. 1.  Returns (codes uint8 [rows, ceil(dim*nbits/8)],
     scale_f16 uint16 [rows], bias_f16 uint16 [rows]) and, if `return_search`, also
     (loss float32 [rows], ij int32 [rows, 2])."""
     lib = _load()
     t, dtype = _as_table(table)
     rows, dim = t.shape
-    codes = np.zeros((rows, (dim + 1) // 2), dtype=np.uint8)
+    codes = np.zeros((rows, packed_bytes(dim, nbits)), dtype=np.uint8)
     scale = np.zeros(rows, dtype=np.uint16)
     bias = np.zeros(rows, dtype=np.uint16)
     loss = np.zeros(rows, dtype=np.float32)
     ij = np.zeros((rows, 2), dtype=np.int32)
     rc = lib.e4q_oracle_quantize_rowwise_greedy(_ptr(t), dtype, rows, dim, dim, int(n_bins),
                                                 float(ratio), int(bool(literal_alg1)), _ptr(codes),
-                                                _ptr(scale), _ptr(bias), _ptr(loss), _ptr(ij))
+                                                _ptr(scale), _ptr(bias), _ptr(loss), _ptr(ij), int(nbits))
     if rc != 0:
         raise ValueError("oracle rejected the arguments")
     if return_search:
@@ -142,33 +148,33 @@ def quantize_rowwise_greedy(table: np.ndarray, n_bins: int = 200, ratio: float =
     return codes, scale, bias
 
 
-def range_loss(x: np.ndarray, lo: float, hi: float) -> float:
+def range_loss(x: np.ndarray, lo: float, hi: float, nbits: int = 4) -> float:
     """Eq. 2 for one row and an explicit range, in the oracle's binary32 arithmetic."""
     x = np.ascontiguousarray(x, dtype=np.float32)
     return float(_load().e4q_oracle_range_loss(_ptr(x), x.size, float(np.float32(lo)),
-                                               float(np.float32(hi))))
+                                               float(np.float32(hi)), int(nbits)))
 
 
-def brute_force_row(x: np.ndarray, n_bins: int, n_iter_: int):
+def brute_force_row(x: np.ndarray, n_bins: int, n_iter_: int, nbits: int = 4):
     """Minimum of Eq. 2 over every (i, j), i + j <= n_iter, of Algorithm 1's grid."""
     x = np.ascontiguousarray(x, dtype=np.float32)
     loss = ctypes.c_float()
     bi, bj = ctypes.c_int32(), ctypes.c_int32()
     rc = _load().e4q_oracle_brute_force_row(_ptr(x), x.size, int(n_bins), int(n_iter_),
-                                            ctypes.byref(loss), ctypes.byref(bi), ctypes.byref(bj))
+                                            ctypes.byref(loss), ctypes.byref(bi), ctypes.byref(bj), int(nbits))
     if rc != 0:
         raise ValueError("oracle rejected the arguments")
     return float(loss.value), int(bi.value), int(bj.value)
 
 
-def dequantize(codes: np.ndarray, scale_f16: np.ndarray, bias_f16: np.ndarray, dim: int) -> np.ndarray:
+def dequantize(codes: np.ndarray, scale_f16: np.ndarray, bias_f16: np.ndarray, dim: int, nbits: int = 4) -> np.ndarray:
     codes = np.ascontiguousarray(codes, dtype=np.uint8)
     scale_f16 = np.ascontiguousarray(scale_f16, dtype=np.uint16)
     bias_f16 = np.ascontiguousarray(bias_f16, dtype=np.uint16)
     rows = codes.shape[0]
-    assert codes.shape[1] == (dim + 1) // 2
+    assert codes.shape[1] == packed_bytes(dim, nbits)
     out = np.empty((rows, dim), dtype=np.float32)
-    rc = _load().e4q_oracle_dequantize(_ptr(codes), _ptr(scale_f16), _ptr(bias_f16), rows, dim, _ptr(out))
+    rc = _load().e4q_oracle_dequantize(_ptr(codes), _ptr(scale_f16), _ptr(bias_f16), rows, dim, _ptr(out), int(nbits))
     if rc != 0:
         raise ValueError("oracle rejected the arguments")
     return out
@@ -236,10 +242,11 @@ def fuse_rows(codes: np.ndarray, scale_f16: np.ndarray, bias_f16: np.ndarray, di
     return out
 
 
-def unpack_codes(codes: np.ndarray, dim: int) -> np.ndarray:
-    """Nibbles of a packed code array: low nibble = even element, high nibble = odd element."""
+def unpack_codes(codes: np.ndarray, dim: int, nbits: int = 4) -> np.ndarray:
+    """Codes of a packed array: 8/nbits per byte, the first element in the lowest bits."""
     codes = np.asarray(codes, dtype=np.uint8)
-    out = np.empty((codes.shape[0], codes.shape[1] * 2), dtype=np.uint8)
-    out[:, 0::2] = codes & 0xF
-    out[:, 1::2] = codes >> 4
+    per = 8 // nbits
+    out = np.empty((codes.shape[0], codes.shape[1] * per), dtype=np.uint8)
+    for s_ in range(per):
+        out[:, s_::per] = (codes >> (s_ * nbits)) & ((1 << nbits) - 1)
     return out[:, :dim]

@@ -34,7 +34,10 @@
  *   - the best (xmin, xmax) is tracked as a PAIR together with its loss
  *     ("joint" tracking).  Algorithm 1 as printed updates only one of the two
  *     on an improvement; `literal_alg1 != 0` reproduces that bookkeeping;
- *   - low nibble = even element, high nibble = odd element.
+ *   - codes are packed 8/n per byte, the first element in the lowest bits (n = 4: low nibble =
+ *     even element, high nibble = odd element);
+ *   - n = 4 is the paper's subject; n = 8 (its ASYM-8BITS baseline) and n = 2 run through the
+ *     same code with 2^n - 1 levels.
  *
  * Pins (see tests): exact 16-point grids, never worse than min/max,
  * brute force over the (i, j) grid, exact rational re-execution of
@@ -49,7 +52,11 @@
 #include <stdlib.h>
 #include <string.h>
 
-#define E4Q_QMAX 15.0f /* 2^n - 1 with n = 4 (Eq. 1) */
+/* Largest code, 2^n - 1 (Eq. 1); n = 4 is the paper's subject, n = 8 its ASYM-8BITS baseline. */
+static float qmax_of(int nbits) { return (float)((1 << nbits) - 1); }
+static int nbits_ok(int nbits) { return nbits == 2 || nbits == 4 || nbits == 8; }
+/* Codes are packed 8/n per byte, element k in bits [(k mod 8/n) * n, +n) of byte k / (8/n). */
+static int64_t packed_bytes(int dim, int nbits) { int per = 8 / nbits; return (dim + per - 1) / per; }
 
 /* ------------------------------------------------------------------ */
 /* binary16 <-> binary32, written out so that it can be audited.       */
@@ -117,22 +124,22 @@ static float round_through_f16(float f) { return e4q_oracle_f16_to_f32(e4q_oracl
 /* Eq. 1 on one element, for stored parameters (scale, bias).          */
 /* ------------------------------------------------------------------ */
 
-/* x_int of Eq. 1, as a float in {0, ..., 15}.  `inv` is 1/scale, or unused when scale == 0. */
-static float quantize_elem(float x, float scale, float bias, float inv)
+/* x_int of Eq. 1, as a float in {0, ..., qmax}.  `inv` is 1/scale, or unused when scale == 0. */
+static float quantize_elem(float x, float scale, float bias, float inv, float qmax)
 {
     if (scale == 0.0f)
         return 0.0f; /* degenerate range: one grid point, code 0 */
     float t = (x - bias) * inv; /* subtract, then multiply: two roundings */
     float q = rintf(t);         /* round-half-to-even (default rounding mode) */
     if (q < 0.0f) q = 0.0f;     /* x below xmin is clipped to xmin */
-    if (q > E4Q_QMAX) q = E4Q_QMAX; /* x above xmax is clipped to xmax */
+    if (q > qmax) q = qmax;     /* x above xmax is clipped to xmax */
     return q;
 }
 
 /* The parameters that would be stored for the range [lo, hi] (Eq. 1, FP16 storage). */
-static void stored_params(float lo, float hi, float *scale, float *bias)
+static void stored_params(float lo, float hi, float qmax, float *scale, float *bias)
 {
-    float scale32 = (hi - lo) / E4Q_QMAX;
+    float scale32 = (hi - lo) / qmax;
     *scale = round_through_f16(scale32);
     *bias = round_through_f16(lo);
 }
@@ -156,13 +163,13 @@ static float tree_sum(float *s, int d, int p)
 }
 
 /* Eq. 2 for the range [lo, hi]: || X - Q(X, lo, hi) ||_2^2.  `work` holds next_pow2(d) floats. */
-static float range_loss(const float *x, int d, float lo, float hi, float *work)
+static float range_loss(const float *x, int d, float lo, float hi, float qmax, float *work)
 {
     float scale, bias;
-    stored_params(lo, hi, &scale, &bias);
+    stored_params(lo, hi, qmax, &scale, &bias);
     float inv = (scale == 0.0f) ? 0.0f : 1.0f / scale;
     for (int k = 0; k < d; ++k) {
-        float q = quantize_elem(x[k], scale, bias, inv);
+        float q = quantize_elem(x[k], scale, bias, inv, qmax);
         float xh = fmaf(q, scale, bias); /* dequantizer of Eq. 1 */
         float e = x[k] - xh;
         work[k] = e * e;
@@ -195,7 +202,7 @@ typedef struct {
 } greedy_result;
 
 static greedy_result greedy_row(const float *x, int d, int32_t n_bins, int32_t n_iter,
-                                int literal_alg1, float *work)
+                                int literal_alg1, float qmax, float *work)
 {
     float lo0 = x[0], hi0 = x[0];
     for (int k = 1; k < d; ++k) {
@@ -206,7 +213,7 @@ static greedy_result greedy_row(const float *x, int d, int32_t n_bins, int32_t n
     if (hi0 == lo0) /* constant row: stepsize is 0 and the loop of Algorithm 1 never runs */
         return best;
 
-    best.loss = range_loss(x, d, lo0, hi0, work);
+    best.loss = range_loss(x, d, lo0, hi0, qmax, work);
     float stepsize = (hi0 - lo0) / (float)n_bins;
     float cur_min = lo0, cur_max = hi0;
     int32_t i = 0, j = 0;
@@ -214,8 +221,8 @@ static greedy_result greedy_row(const float *x, int d, int32_t n_bins, int32_t n
     for (int32_t it = 0; it < n_iter; ++it) {
         float next_min = cur_min + stepsize;
         float next_max = cur_max - stepsize;
-        float loss_l = range_loss(x, d, next_min, cur_max, work);
-        float loss_r = range_loss(x, d, cur_min, next_max, work);
+        float loss_l = range_loss(x, d, next_min, cur_max, qmax, work);
+        float loss_r = range_loss(x, d, cur_min, next_max, qmax, work);
         if (loss_l < loss_r) {
             cur_min = next_min;
             ++i;
@@ -239,21 +246,27 @@ static greedy_result greedy_row(const float *x, int d, int32_t n_bins, int32_t n
     return best;
 }
 
-/* Codes of Eq. 1 for the range [lo, hi], packed two per byte, plus the stored parameters. */
-static void encode_row(const float *x, int d, float lo, float hi, uint8_t *codes,
+/* Codes of Eq. 1 for the range [lo, hi], packed 8/nbits per byte, plus the stored parameters. */
+static void encode_row(const float *x, int d, float lo, float hi, int nbits, uint8_t *codes,
                        uint16_t *scale_f16, uint16_t *bias_f16)
 {
-    float scale32 = (hi - lo) / E4Q_QMAX;
+    float qmax = qmax_of(nbits);
+    float scale32 = (hi - lo) / qmax;
     *scale_f16 = e4q_oracle_f32_to_f16(scale32);
     *bias_f16 = e4q_oracle_f32_to_f16(lo);
     float scale = e4q_oracle_f16_to_f32(*scale_f16);
     float bias = e4q_oracle_f16_to_f32(*bias_f16);
     float inv = (scale == 0.0f) ? 0.0f : 1.0f / scale;
-    int nbytes = (d + 1) / 2;
-    for (int b = 0; b < nbytes; ++b) {
-        unsigned q0 = (unsigned)quantize_elem(x[2 * b], scale, bias, inv);
-        unsigned q1 = (2 * b + 1 < d) ? (unsigned)quantize_elem(x[2 * b + 1], scale, bias, inv) : 0u;
-        codes[b] = (uint8_t)(q0 | (q1 << 4));
+    int per = 8 / nbits;
+    int64_t nbytes = packed_bytes(d, nbits);
+    for (int64_t b = 0; b < nbytes; ++b) {
+        unsigned byte = 0;
+        for (int s = 0; s < per; ++s) {
+            int64_t k = b * per + s;
+            unsigned q = (k < d) ? (unsigned)quantize_elem(x[k], scale, bias, inv, qmax) : 0u;
+            byte |= q << (s * nbits); /* lowest bits = first element */
+        }
+        codes[b] = (uint8_t)byte;
     }
 }
 
@@ -268,10 +281,10 @@ static void widen_row(const void *table, int dtype, int64_t row, int64_t row_str
 }
 
 /*
- * Row-wise greedy 4-bit quantization of a table (Algorithm 1 per row, then Eq. 1).
+ * Row-wise greedy n-bit quantization of a table (Algorithm 1 per row, then Eq. 1); n = 2, 4 or 8.
  *   table       rows x dim, row-major with `row_stride` elements between rows,
  *               dtype 0 = binary32, 1 = binary16
- *   codes       rows x ceil(dim/2) bytes out
+ *   codes       rows x ceil(dim * nbits / 8) bytes out
  *   scale_f16, bias_f16   rows binary16 bit patterns out
  *   loss_out    optional (may be NULL): rows floats, the search's loss of the result
  *               (for constant rows: 0)
@@ -281,8 +294,10 @@ static void widen_row(const void *table, int dtype, int64_t row, int64_t row_str
 int e4q_oracle_quantize_rowwise_greedy(const void *table, int dtype, int64_t rows, int32_t dim,
                                        int64_t row_stride, int32_t n_bins, float ratio,
                                        int literal_alg1, uint8_t *codes, uint16_t *scale_f16,
-                                       uint16_t *bias_f16, float *loss_out, int32_t *ij_out)
+                                       uint16_t *bias_f16, float *loss_out, int32_t *ij_out, int32_t nbits)
 {
+    if (!nbits_ok(nbits)) return -1;
+    float qmax = qmax_of(nbits);
     if (!table || !codes || !scale_f16 || !bias_f16 || rows < 0 || dim <= 0 || n_bins < 1 ||
         !(ratio >= 0.0f && ratio < 1.0f) || row_stride < dim || (dtype != 0 && dtype != 1))
         return -1;
@@ -291,11 +306,11 @@ int e4q_oracle_quantize_rowwise_greedy(const void *table, int dtype, int64_t row
     float *x = (float *)malloc((size_t)dim * sizeof(float));
     float *work = (float *)malloc((size_t)p * sizeof(float));
     if (!x || !work) { free(x); free(work); return -1; }
-    int64_t nbytes = (dim + 1) / 2;
+    int64_t nbytes = packed_bytes(dim, nbits);
     for (int64_t r = 0; r < rows; ++r) {
         widen_row(table, dtype, r, row_stride, dim, x);
-        greedy_result g = greedy_row(x, dim, n_bins, n_iter, literal_alg1, work);
-        encode_row(x, dim, g.xmin, g.xmax, codes + r * nbytes, scale_f16 + r, bias_f16 + r);
+        greedy_result g = greedy_row(x, dim, n_bins, n_iter, literal_alg1, qmax, work);
+        encode_row(x, dim, g.xmin, g.xmax, nbits, codes + r * nbytes, scale_f16 + r, bias_f16 + r);
         if (loss_out) loss_out[r] = g.loss;
         if (ij_out) { ij_out[2 * r] = g.i; ij_out[2 * r + 1] = g.j; }
     }
@@ -305,10 +320,10 @@ int e4q_oracle_quantize_rowwise_greedy(const void *table, int dtype, int64_t row
 }
 
 /* Eq. 2 of one row for an explicit range, in the oracle's arithmetic (for tests). */
-float e4q_oracle_range_loss(const float *x, int32_t dim, float lo, float hi)
+float e4q_oracle_range_loss(const float *x, int32_t dim, float lo, float hi, int32_t nbits)
 {
     float *work = (float *)malloc((size_t)next_pow2(dim) * sizeof(float));
-    float l = range_loss(x, dim, lo, hi, work);
+    float l = range_loss(x, dim, lo, hi, qmax_of(nbits), work);
     free(work);
     return l;
 }
@@ -319,9 +334,10 @@ float e4q_oracle_range_loss(const float *x, int32_t dim, float lo, float hi)
  * algorithm forms them).  Writes the smallest loss and one (i, j) that attains it.
  */
 int e4q_oracle_brute_force_row(const float *x, int32_t dim, int32_t n_bins, int32_t n_iter,
-                               float *best_loss, int32_t *best_i, int32_t *best_j)
+                               float *best_loss, int32_t *best_i, int32_t *best_j, int32_t nbits)
 {
-    if (!x || dim <= 0 || n_bins < 1 || n_iter < 0) return -1;
+    if (!x || dim <= 0 || n_bins < 1 || n_iter < 0 || !nbits_ok(nbits)) return -1;
+    float qmax = qmax_of(nbits);
     float *work = (float *)malloc((size_t)next_pow2(dim) * sizeof(float));
     float lo0 = x[0], hi0 = x[0];
     for (int k = 1; k < dim; ++k) {
@@ -335,7 +351,7 @@ int e4q_oracle_brute_force_row(const float *x, int32_t dim, int32_t n_bins, int3
     for (int32_t i = 0; i <= n_iter; ++i) {
         float hi = hi0;
         for (int32_t j = 0; i + j <= n_iter; ++j) {
-            float l = range_loss(x, dim, lo, hi, work);
+            float l = range_loss(x, dim, lo, hi, qmax, work);
             if (l < bl) { bl = l; bi = i; bj = j; }
             hi = hi - stepsize;
         }
@@ -348,16 +364,18 @@ int e4q_oracle_brute_force_row(const float *x, int32_t dim, int32_t n_bins, int3
 
 /* x_float = scale * x_int + bias (sentence after Eq. 1), one fused multiply-add per element. */
 int e4q_oracle_dequantize(const uint8_t *codes, const uint16_t *scale_f16, const uint16_t *bias_f16,
-                          int64_t rows, int32_t dim, float *out)
+                          int64_t rows, int32_t dim, float *out, int32_t nbits)
 {
-    if (!codes || !scale_f16 || !bias_f16 || !out || rows < 0 || dim <= 0) return -1;
-    int64_t nbytes = (dim + 1) / 2;
+    if (!codes || !scale_f16 || !bias_f16 || !out || rows < 0 || dim <= 0 || !nbits_ok(nbits)) return -1;
+    int per = 8 / nbits;
+    unsigned mask = (1u << nbits) - 1u;
+    int64_t nbytes = packed_bytes(dim, nbits);
     for (int64_t r = 0; r < rows; ++r) {
         float scale = e4q_oracle_f16_to_f32(scale_f16[r]);
         float bias = e4q_oracle_f16_to_f32(bias_f16[r]);
         for (int k = 0; k < dim; ++k) {
-            uint8_t byte = codes[r * nbytes + k / 2];
-            unsigned q = (k & 1) ? (byte >> 4) : (byte & 0xfu);
+            uint8_t byte = codes[r * nbytes + k / per];
+            unsigned q = (byte >> ((k % per) * nbits)) & mask;
             out[r * dim + k] = fmaf((float)q, scale, bias);
         }
     }

@@ -21,17 +21,17 @@ import numpy as np
 F32 = np.float32
 
 
-def _stored(lo: F32, hi: F32):
-    scale32 = F32(F32(hi - lo) / F32(15.0))
+def _stored(lo: F32, hi: F32, qmax: float = 15.0):
+    scale32 = F32(F32(hi - lo) / F32(qmax))
     return F32(np.float16(scale32)), F32(np.float16(lo))
 
 
-def _codes_f32(x: np.ndarray, scale: F32, bias: F32) -> np.ndarray:
+def _codes_f32(x: np.ndarray, scale: F32, bias: F32, qmax: float = 15.0) -> np.ndarray:
     if scale == 0:
         return np.zeros_like(x)
     inv = F32(F32(1.0) / scale)
     t = ((x - bias).astype(F32) * inv).astype(F32)
-    return np.clip(np.rint(t), F32(0), F32(15)).astype(F32)
+    return np.clip(np.rint(t), F32(0), F32(qmax)).astype(F32)
 
 
 def _pair_tree(s: np.ndarray) -> F32:
@@ -45,16 +45,16 @@ def _pair_tree(s: np.ndarray) -> F32:
     return F32(v[0])
 
 
-def loss(x: np.ndarray, lo: F32, hi: F32) -> F32:
-    scale, bias = _stored(lo, hi)
-    q = _codes_f32(x, scale, bias)
+def loss(x: np.ndarray, lo: F32, hi: F32, qmax: float = 15.0) -> F32:
+    scale, bias = _stored(lo, hi, qmax)
+    q = _codes_f32(x, scale, bias, qmax)
     # fmaf(q, scale, bias): q*scale + bias is exact in float64, one rounding to float32
     xh = (q.astype(np.float64) * np.float64(scale) + np.float64(bias)).astype(F32)
     e = (x - xh).astype(F32)
     return _pair_tree((e * e).astype(F32))
 
 
-def greedy_row(x: np.ndarray, n_bins: int, ratio: float, literal_alg1: bool = False):
+def greedy_row(x: np.ndarray, n_bins: int, ratio: float, literal_alg1: bool = False, qmax: float = 15.0):
     x = x.astype(F32)
     lo0, hi0 = F32(x.min()), F32(x.max())
     if lo0 == hi0:
@@ -63,10 +63,10 @@ def greedy_row(x: np.ndarray, n_bins: int, ratio: float, literal_alg1: bool = Fa
     n_iter = int(min(max(math.ceil(br - br * 2.0 ** -22), 0), n_bins - 1))
     step = F32(F32(hi0 - lo0) / F32(n_bins))
     cur_lo, cur_hi, i, j = lo0, hi0, 0, 0
-    best = [lo0, hi0, loss(x, lo0, hi0), 0, 0]
+    best = [lo0, hi0, loss(x, lo0, hi0, qmax), 0, 0]
     for _ in range(n_iter):
         nlo, nhi = F32(cur_lo + step), F32(cur_hi - step)
-        ll, lr = loss(x, nlo, cur_hi), loss(x, cur_lo, nhi)
+        ll, lr = loss(x, nlo, cur_hi, qmax), loss(x, cur_lo, nhi, qmax)
         if ll < lr:
             cur_lo, i = nlo, i + 1
             if ll < best[2]:
@@ -83,22 +83,24 @@ def greedy_row(x: np.ndarray, n_bins: int, ratio: float, literal_alg1: bool = Fa
 
 
 def quantize_rowwise_greedy(table: np.ndarray, n_bins: int = 200, ratio: float = 0.16,
-                            literal_alg1: bool = False):
+                            literal_alg1: bool = False, nbits: int = 4):
     rows, dim = table.shape
-    codes = np.zeros((rows, (dim + 1) // 2), dtype=np.uint8)
+    qmax, per = float(2 ** nbits - 1), 8 // nbits
+    nbytes = (dim + per - 1) // per
+    codes = np.zeros((rows, nbytes), dtype=np.uint8)
     scale_bits = np.zeros(rows, dtype=np.uint16)
     bias_bits = np.zeros(rows, dtype=np.uint16)
     losses = np.zeros(rows, dtype=F32)
     ij = np.zeros((rows, 2), dtype=np.int32)
     for r in range(rows):
         x = table[r].astype(F32)
-        lo, hi, l, i, j = greedy_row(x, n_bins, ratio, literal_alg1)
-        scale, bias = _stored(lo, hi)
+        lo, hi, l, i, j = greedy_row(x, n_bins, ratio, literal_alg1, qmax)
+        scale, bias = _stored(lo, hi, qmax)
         scale_bits[r] = np.float16(scale).view(np.uint16)
         bias_bits[r] = np.float16(bias).view(np.uint16)
-        q = _codes_f32(x, scale, bias).astype(np.uint8)
-        if dim % 2:
-            q = np.concatenate([q, np.zeros(1, dtype=np.uint8)])
-        codes[r] = q[0::2] | (q[1::2] << 4)
+        q = np.zeros(nbytes * per, dtype=np.uint8)
+        q[:dim] = _codes_f32(x, scale, bias, qmax).astype(np.uint8)
+        for s_ in range(per):
+            codes[r] |= q[s_::per] << (s_ * nbits)
         losses[r], ij[r, 0], ij[r, 1] = l, i, j
     return codes, scale_bits, bias_bits, losses, ij

@@ -44,27 +44,27 @@ def quantize(X, xmin: Fraction, xmax: Fraction, nbits: int = 4):
     return codes, ties, scale
 
 
-def loss(X, xmin: Fraction, xmax: Fraction) -> Fraction:
+def loss(X, xmin: Fraction, xmax: Fraction, nbits: int = 4) -> Fraction:
     """Eq. 2: squared l2 distance between X and its quantize->dequantize image."""
-    codes, _, scale = quantize(X, xmin, xmax)
+    codes, _, scale = quantize(X, xmin, xmax, nbits)
     return sum(((x - (scale * q + xmin)) ** 2 for x, q in zip(X, codes)), Fraction(0))
 
 
-def greedy(X, b: int, r: Fraction, literal: bool = False):
+def greedy(X, b: int, r: Fraction, literal: bool = False, nbits: int = 4):
     """Algorithm 1.  `literal=False` stores the pair (cur_min, cur_max) with every improvement;
     `literal=True` updates only the bound that moved, as the printed listing does.
     Returns (xmin, xmax, loss, n_trips, largest loss evaluated)."""
     X = [Fraction(x) for x in X]
     xmin = cur_min = min(X)
     xmax = cur_max = max(X)
-    best = loss(X, xmin, xmax)
+    best = loss(X, xmin, xmax, nbits)
     stepsize = (xmax - xmin) / b
     min_steps = b * (1 - r) * stepsize
     trips, biggest = 0, best
     while cur_min + min_steps < cur_max:
         trips += 1
-        loss_l = loss(X, cur_min + stepsize, cur_max)
-        loss_r = loss(X, cur_min, cur_max - stepsize)
+        loss_l = loss(X, cur_min + stepsize, cur_max, nbits)
+        loss_r = loss(X, cur_min, cur_max - stepsize, nbits)
         biggest = max(biggest, loss_l, loss_r)
         if loss_l < loss_r:
             cur_min = cur_min + stepsize
@@ -81,15 +81,16 @@ def greedy(X, b: int, r: Fraction, literal: bool = False):
     return xmin, xmax, best, trips, biggest
 
 
-def lattice_row(rng: np.random.Generator, d: int, b: int, shift: int = 0, outliers: int = 2) -> np.ndarray:
-    """Integer-valued row whose range is exactly 15*b*2^shift, centred near zero.
+def lattice_row(rng: np.random.Generator, d: int, b: int, shift: int = 0, outliers: int = 2,
+                levels: int = 15) -> np.ndarray:
+    """Integer-valued row whose range is exactly levels*b*2^shift (levels = 2^n - 1), centred near zero.
 
     Then stepsize = 15*2^shift, every candidate bound is an integer, every candidate scale
     (b - i - j)*2^shift is an integer with at most 11 significant bits, and all errors are
     integers: binary16 storage of scale and bias and every binary32 operation of the loss are
     exact as long as the losses stay below 2^24 (the caller checks that)."""
     unit = 1 << shift
-    span = 15 * b * unit
+    span = levels * b * unit
     lo = -(span // 2 // unit) * unit
     hi = lo + span
     # bulk of the row in the inner part of the range, a few points out at the ends

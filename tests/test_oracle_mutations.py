@@ -40,25 +40,25 @@ SLS_MUTANTS = {
 }
 
 MUTANTS = {
-    "sixteen_levels": ("#define E4Q_QMAX 15.0f", "#define E4Q_QMAX 16.0f"),
+    "sixteen_levels": ("return (float)((1 << nbits) - 1); }", "return (float)(1 << nbits); }"),
     "tie_moves_lower_bound": ("if (loss_l < loss_r) {", "if (loss_l <= loss_r) {"),
     "later_equal_loss_wins": ("if (loss_r < best.loss) {", "if (loss_r <= best.loss) {"),
     "upper_bound_moves_up": ("float next_max = cur_max - stepsize;", "float next_max = cur_max + stepsize;"),
     "round_half_up": ("float q = rintf(t);", "float q = floorf(t + 0.5f);"),
     "truncate": ("float q = rintf(t);", "float q = truncf(t);"),
     "strided_sum_tree": ("s[i] = s[2 * i] + s[2 * i + 1];", "s[i] = s[i] + s[i + m / 2];"),
-    "nibbles_swapped": ("codes[b] = (uint8_t)(q0 | (q1 << 4));", "codes[b] = (uint8_t)(q1 | (q0 << 4));"),
+    "nibbles_swapped": ("byte |= q << (s * nbits);", "byte |= q << ((per - 1 - s) * nbits);"),
     "search_ignores_fp16_storage": ("*scale = round_through_f16(scale32);", "*scale = scale32;"),
-    "no_upper_clamp": ("if (q > E4Q_QMAX) q = E4Q_QMAX;", ""),
+    "no_upper_clamp": ("if (q > qmax) q = qmax;", ""),
     "no_lower_clamp": ("if (q < 0.0f) q = 0.0f;", "if (q < 0.0f) q = -q;"),
     "step_off_by_one": ("float stepsize = (hi0 - lo0) / (float)n_bins;\n    float cur_min",
                         "float stepsize = (hi0 - lo0) / (float)(n_bins - 1);\n    float cur_min"),
     "floor_trip_count": ("double t = ceil(br - br * 0x1p-22);", "double t = floor(br);"),
-    "start_not_a_candidate": ("best.loss = range_loss(x, d, lo0, hi0, work);", "best.loss = INFINITY;"),
+    "start_not_a_candidate": ("best.loss = range_loss(x, d, lo0, hi0, qmax, work);", "best.loss = INFINITY;"),
     "literal_bookkeeping_by_default": ("if (!literal_alg1) { best.xmax = cur_max; best.j = j; }",
                                        "if (literal_alg1) { best.xmax = cur_max; best.j = j; }"),
-    "dequantize_nibbles_swapped": ("unsigned q = (k & 1) ? (byte >> 4) : (byte & 0xfu);\n            out[r * dim + k] = fmaf",
-                                   "unsigned q = (k & 1) ? (byte & 0xfu) : (byte >> 4);\n            out[r * dim + k] = fmaf"),
+    "dequantize_nibbles_swapped": ("unsigned q = (byte >> ((k % per) * nbits)) & mask;",
+                                   "unsigned q = (byte >> ((per - 1 - k % per) * nbits)) & mask;"),
     "bias_is_not_xmin": ("*bias_f16 = e4q_oracle_f32_to_f16(lo);", "*bias_f16 = e4q_oracle_f32_to_f16(hi);"),
     "error_not_squared": ("work[k] = e * e;", "work[k] = fabsf(e);"),
     "f16_ties_away": ("if (rem > 0x1000u || (rem == 0x1000u && (h & 1u)))", "if (rem >= 0x1000u)"),

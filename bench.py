@@ -11,7 +11,7 @@ de-quantizer.  `--workload mixture_2M_x_64_kmeans16` times the codebook variant 
 `--workload lookup_10M_x_128_sls` times the 4-bit SparseLengthsSum lookup over the quantized
 table (2^20 bags of 1..64 uniformly random rows; bound by HBM gathers);
 `--workload batch_26_half_tables` times the batch entry point on 26 binary16 tables.  `--rows`,
-`--dim`, `--n-bins`, `--ratio`, `--half` vary the single-table workloads (for example `--ratio 0`
+`--dim`, `--n-bins`, `--ratio`, `--half`, `--nbits` vary the single-table workloads (for example `--ratio 0`
 is plain min/max quantization, which is bound by HBM instead of VALU issue).
 
 Prints ONE JSON line.  `value` is rows per second over whole steps; `kernels` gives each kernel's
@@ -256,6 +256,7 @@ def main() -> int:
     ap.add_argument("--n-bins", type=int, default=0, help="override b of Algorithm 1")
     ap.add_argument("--ratio", type=float, default=-1.0, help="override r of Algorithm 1 (0 = plain min/max)")
     ap.add_argument("--half", action="store_true", help="feed the table as binary16")
+    ap.add_argument("--nbits", type=int, default=4, choices=[2, 4, 8], help="code width of the uniform quantizer")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy kernel three times, so that a "
@@ -295,21 +296,22 @@ def main() -> int:
     if method == "greedy":
         n_bins, ratio = params["n_bins"], params["ratio"]
         n_iter = e4q.greedy_iterations(n_bins, ratio)
-        out = e4q.alloc_outputs(rows, dim, table.device)
-        quantize = lambda: e4q.quantize_rowwise_greedy(table, n_bins, ratio, out=out)  # noqa: E731
-        dequantize = lambda: e4q.dequantize(out[0], out[1], out[2], dim, out=xh)  # noqa: E731
+        nbits = args.nbits
+        out = e4q.alloc_outputs(rows, dim, table.device, nbits)
+        quantize = lambda: e4q.quantize_rowwise_greedy(table, n_bins, ratio, nbits=nbits, out=out)  # noqa: E731
+        dequantize = lambda: e4q.dequantize(out[0], out[1], out[2], dim, nbits=nbits, out=xh)  # noqa: E731
         # the library takes one row per lane when there are enough rows and dim is 8, 16, ..., 128
         rpl = n_iter > 0 and (rows + 63) // 64 >= 512 and dim % 8 == 0 and dim <= 128
         q_name, dq_name = ("greedy_rpl_kernel" if rpl else "greedy_swl_kernel"), "dequantize_w4_kernel"
         ops_per_row = greedy_lane_ops_per_row(dim, n_iter)
-        out_bytes_per_row = (dim + 1) // 2 + 4
-        config = {"n_bins": n_bins, "ratio": ratio, "candidate_ranges_per_row": 1 + 2 * n_iter, "nbits": 4,
+        out_bytes_per_row = e4q.packed_bytes(dim, nbits) + 4
+        config = {"n_bins": n_bins, "ratio": ratio, "candidate_ranges_per_row": 1 + 2 * n_iter, "nbits": nbits,
                   "step": "quantize_rowwise_greedy + dequantize, table resident in HBM"}
-        metric = "rows quantized/sec (greedy 4-bit)"
+        metric = f"rows quantized/sec (greedy {nbits}-bit)"
 
         def run_oracle(t):
             import oracle
-            return oracle.quantize_rowwise_greedy(t, n_bins, ratio)
+            return oracle.quantize_rowwise_greedy(t, n_bins, ratio, nbits=nbits)
     else:
         iters = params["lloyd_iters"]
         out = (torch.empty((rows, (dim + 1) // 2), dtype=torch.uint8, device=table.device),
@@ -393,7 +395,7 @@ def main() -> int:
             "hbm_achieved_GBps": q_bytes / (q_ms * 1e-3) / 1e9,
             "hbm_frac": q_bytes / (q_ms * 1e-3) / PEAK_HBM_BYTES,
             "traffic": read_traffic(f"{q_name}_{args.workload}_hbm_traffic.txt")
-            if not (args.rows or args.dim or args.n_bins or args.ratio >= 0 or args.half) else None,
+            if not (args.rows or args.dim or args.n_bins or args.ratio >= 0 or args.half or args.nbits != 4) else None,
         },
     }
     if method == "greedy" and n_iter == 0:  # plain min/max: one pass over the data, bound by HBM

@@ -17,9 +17,10 @@
  *    or signal crosses the boundary.  Arguments are validated before anything is launched, so
  *    a failed call has written nothing.  rows == 0 is a successful no-op.
  *  - Tables are row-major.  `row_stride` is the distance between consecutive rows in ELEMENTS
- *    (>= dim).  Packed codes are dense: ceil(dim/2) bytes per row, no padding between rows;
- *    element 2k sits in the low nibble and element 2k+1 in the high nibble of byte k; for odd
- *    dim the last high nibble is 0.  scale, bias and codebook entries are IEEE binary16 bit
+ *    (>= dim).  Packed codes are dense: 8/nbits codes per byte, ceil(dim * nbits / 8) bytes per
+ *    row, no padding between rows; the first element of a byte sits in its lowest bits (nbits = 4:
+ *    element 2k in the low nibble and element 2k+1 in the high nibble of byte k); unused bits of a
+ *    row's last byte are 0.  scale, bias and codebook entries are IEEE binary16 bit
  *    patterns stored as uint16_t.
  *  - Inputs containing NaN or infinities, and rows whose minimum or range exceeds the
  *    binary16 range (65504), give unspecified codes and parameters (never a fault).
@@ -37,7 +38,7 @@ extern "C" {
 #define E4Q_OK 0
 #define E4Q_ERR_NULL_POINTER (-1)   /* a required pointer is NULL */
 #define E4Q_ERR_BAD_SHAPE (-2)      /* rows < 0, dim <= 0, dim > E4Q_MAX_DIM, row_stride < dim */
-#define E4Q_ERR_BAD_NBITS (-3)      /* nbits != 4 */
+#define E4Q_ERR_BAD_NBITS (-3)      /* nbits not in {2, 4, 8} (quantizer, dequantizer) or != 4 (lookup operator) */
 #define E4Q_ERR_BAD_SEARCH (-4)     /* n_bins < 1, ratio outside [0, 1), ratio NaN, lloyd_iters < 0 */
 #define E4Q_ERR_BAD_DTYPE (-5)      /* dtype is neither E4Q_F32 nor E4Q_F16; index_bytes is neither 4 nor 8 */
 #define E4Q_ERR_LAUNCH (-6)         /* HIP reported an error when the kernel was enqueued */
@@ -51,7 +52,7 @@ extern "C" {
 #define E4Q_MAX_DIM 4096
 
 /*
- * Row-wise uniform 4-bit quantization with greedy search of the clipping range
+ * Row-wise uniform n-bit quantization (n = 4 in the paper) with greedy search of the clipping range
  * (Algorithm 1; quantizer and stored parameters of Eq. 1; loss of Eq. 2; binary16 scale and
  * bias as in the "(FP16)" variants of Section 4).
  *
@@ -60,18 +61,19 @@ extern "C" {
  * against "upper bound down one step" by the squared quantize->dequantize error of the row,
  * move the bound with the smaller error (ties move the upper bound) and remember the range
  * with the smallest error seen (strictly smaller replaces; the pair of bounds is remembered
- * together).  The row is then encoded with that range: scale = (xmax - xmin)/15 and
- * bias = xmin rounded to binary16, code = clamp(round_half_even((x - bias) * (1/scale)), 0, 15),
+ * together).  The row is then encoded with that range: scale = (xmax - xmin)/(2^nbits - 1) and bias =
+ * xmin rounded to binary16, code = clamp(round_half_even((x - bias) * (1/scale)), 0, 2^nbits - 1),
  * all in binary32.  Candidates are scored with the binary16-rounded parameters, i.e. with
  * what is stored.  ratio == 0 gives plain min/max ("ASYM") quantization.  A row with
  * max == min, or whose scale rounds to 0 in binary16, gets scale 0 and all codes 0.
  *
  *   table       [in]  rows x dim elements of `dtype`, `row_stride` elements between rows
  *   dtype             E4Q_F32 or E4Q_F16 (binary16 inputs are widened exactly)
- *   nbits             must be 4
+ *   nbits             4 (the paper's subject); 8 (its ASYM-8BITS baseline, Section 4) and 2 are
+ *                     accepted too and differ only in the number of levels and the packing
  *   n_bins            b of Algorithm 1 (default in the paper: 200)
  *   ratio             r of Algorithm 1 (default in the paper: 0.16), 0 <= ratio < 1
- *   codes       [out] rows x ceil(dim/2) bytes
+ *   codes       [out] rows x ceil(dim * nbits / 8) bytes
  *   scale_f16   [out] rows binary16 values
  *   bias_f16    [out] rows binary16 values
  */

@@ -18,7 +18,7 @@ def __getattr__(name):
 
         return importlib.import_module(".binding", __name__)
     if name in ("quantize_rowwise_greedy", "quantize_rowwise_greedy_batch", "dequantize", "greedy_iterations",
-                "alloc_outputs", "load_library", "E4QError", "quantize_rowwise_kmeans16", "dequantize_codebook",
+                "alloc_outputs", "packed_bytes", "load_library", "E4QError", "quantize_rowwise_kmeans16", "dequantize_codebook",
                 "sparse_lengths_sum", "fuse_rows", "sparse_lengths_sum_fused", "fused_row_bytes"):
         import importlib
 

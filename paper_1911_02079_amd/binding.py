@@ -126,10 +126,16 @@ def greedy_iterations(n_bins: int, ratio: float) -> int:
     return n
 
 
-def alloc_outputs(rows: int, dim: int, device) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
-    """Output buffers of the layout the library writes: codes uint8 [rows, ceil(dim/2)],
+def packed_bytes(dim: int, nbits: int = 4) -> int:
+    """Bytes of one row of codes: 8/nbits codes per byte."""
+    per = 8 // nbits
+    return (dim + per - 1) // per
+
+
+def alloc_outputs(rows: int, dim: int, device, nbits: int = 4) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
+    """Output buffers of the layout the library writes: codes uint8 [rows, ceil(dim*nbits/8)],
     scale and bias float16 [rows]."""
-    codes = torch.empty((rows, (dim + 1) // 2), dtype=torch.uint8, device=device)
+    codes = torch.empty((rows, packed_bytes(dim, nbits)), dtype=torch.uint8, device=device)
     scale = torch.empty((rows,), dtype=torch.float16, device=device)
     bias = torch.empty((rows,), dtype=torch.float16, device=device)
     return codes, scale, bias
@@ -143,7 +149,7 @@ def quantize_rowwise_greedy(table: torch.Tensor, n_bins: int = 200, ratio: float
     lib = load_library()
     _check_table(table)
     rows, dim = table.shape
-    codes, scale, bias = out if out is not None else alloc_outputs(rows, dim, table.device)
+    codes, scale, bias = out if out is not None else alloc_outputs(rows, dim, table.device, nbits)
     with torch.cuda.device(table.device):
         rc = lib.e4q_quantize_rowwise_greedy(table.data_ptr(), _dtype_code(table), rows, dim,
                                              table.stride(0) if rows > 1 else max(dim, table.stride(0)),
@@ -163,7 +169,7 @@ def quantize_rowwise_greedy_batch(tables: Sequence[torch.Tensor], n_bins: int = 
     for t in tables:
         _check_table(t)
     device = tables[0].device
-    outs = out if out is not None else [alloc_outputs(t.shape[0], t.shape[1], device) for t in tables]
+    outs = out if out is not None else [alloc_outputs(t.shape[0], t.shape[1], device, nbits) for t in tables]
     descs = (TableDesc * len(tables))()
     for d, t, (codes, scale, bias) in zip(descs, tables, outs):
         d.table, d.dtype, d.dim, d.rows = t.data_ptr(), _dtype_code(t), t.shape[1], t.shape[0]
@@ -187,8 +193,10 @@ def dequantize(codes: torch.Tensor, scale_f16: torch.Tensor, bias_f16: torch.Ten
     if not (codes.is_contiguous() and scale_f16.is_contiguous() and bias_f16.is_contiguous()):
         raise ValueError("codes, scale and bias must be dense")
     rows = codes.shape[0]
-    if codes.shape[1] != (dim + 1) // 2 or scale_f16.numel() != rows or bias_f16.numel() != rows:
-        raise ValueError("shapes of codes / scale / bias do not match dim")
+    if nbits not in (2, 4, 8):
+        raise E4QError(-3, load_library().e4q_strerror(-3).decode())
+    if codes.shape[1] != packed_bytes(dim, nbits) or scale_f16.numel() != rows or bias_f16.numel() != rows:
+        raise ValueError("shapes of codes / scale / bias do not match dim and nbits")
     if out is None:
         out = torch.empty((rows, dim), dtype=torch.float32, device=codes.device)
     elif out.dtype != torch.float32 or not out.is_contiguous() or tuple(out.shape) != (rows, dim):

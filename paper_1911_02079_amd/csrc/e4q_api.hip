@@ -22,9 +22,11 @@ int fail_launch(hipError_t err)
 
 inline bool aligned(const void* p, size_t a) { return reinterpret_cast<uintptr_t>(p) % a == 0; }
 
+bool nbits_ok(int32_t nbits) { return nbits == 2 || nbits == 4 || nbits == 8; }
+
 int validate_search(int32_t nbits, int32_t n_bins, float ratio)
 {
-    if (nbits != 4) return E4Q_ERR_BAD_NBITS;
+    if (!nbits_ok(nbits)) return E4Q_ERR_BAD_NBITS;
     if (n_bins < 1 || !(ratio >= 0.0f && ratio < 1.0f)) return E4Q_ERR_BAD_SEARCH;
     return E4Q_OK;
 }
@@ -41,7 +43,7 @@ int validate_table(const void* table, int dtype, int64_t rows, int32_t dim, int6
     return E4Q_OK;
 }
 
-int enqueue_greedy(const void* table, int dtype, int64_t rows, int32_t dim, int64_t row_stride,
+int enqueue_greedy(const void* table, int dtype, int64_t rows, int32_t dim, int64_t row_stride, int32_t nbits,
                    int32_t n_bins, int32_t n_iter, uint8_t* codes, uint16_t* scale_f16,
                    uint16_t* bias_f16, hipStream_t stream)
 {
@@ -58,6 +60,8 @@ int enqueue_greedy(const void* table, int dtype, int64_t rows, int32_t dim, int6
     a.bias_f16 = bias_f16;
     a.vec_loads = (aligned(table, 16) && (row_stride * esz) % 16 == 0) ? 1u : 0u;
     a.vec_stores = aligned(codes, 16) ? 2u : (aligned(codes, 4) ? 1u : 0u);
+    a.nbits = nbits;
+    a.qmax = (float)((1 << nbits) - 1);
 
     // Kernel choice.  One row per lane (rows/64 waves, rows in registers, ~3 % overhead over the
     // algorithmic operation count) is the cheapest way to do the arithmetic and is used whenever the
@@ -112,7 +116,7 @@ int e4q_quantize_rowwise_greedy(const void* table, int dtype, int64_t rows, int3
     if (rc != E4Q_OK) return rc;
     rc = validate_table(table, dtype, rows, dim, row_stride, codes, scale_f16, bias_f16);
     if (rc != E4Q_OK) return rc;
-    return enqueue_greedy(table, dtype, rows, dim, row_stride, n_bins, e4q_greedy_iterations(n_bins, ratio),
+    return enqueue_greedy(table, dtype, rows, dim, row_stride, nbits, n_bins, e4q_greedy_iterations(n_bins, ratio),
                           codes, scale_f16, bias_f16, static_cast<hipStream_t>(hip_stream));
 }
 
@@ -151,6 +155,8 @@ int e4q_quantize_rowwise_greedy_batch(const e4q_table_desc* descs, int32_t n_tab
                 g.n_tables = (int32_t)std::min<size_t>(e4q::kMaxGroupTables, members.size() - first);
                 g.n_iter = n_iter;
                 g.n_bins = (float)n_bins;
+                g.nbits = nbits;
+                g.qmax = (float)((1 << nbits) - 1);
                 uint32_t blocks = 0;
                 for (int32_t k = 0; k < e4q::kMaxGroupTables; ++k) {
                     if (k < g.n_tables) {
@@ -181,7 +187,7 @@ int e4q_quantize_rowwise_greedy_batch(const e4q_table_desc* descs, int32_t n_tab
     for (int32_t t = 0; t < n_tables; ++t) {
         if (done[t]) continue;
         const e4q_table_desc& d = descs[t];
-        rc = enqueue_greedy(d.table, d.dtype, d.rows, d.dim, d.row_stride, n_bins, n_iter, d.codes,
+        rc = enqueue_greedy(d.table, d.dtype, d.rows, d.dim, d.row_stride, nbits, n_bins, n_iter, d.codes,
                             d.scale_f16, d.bias_f16, stream);
         if (rc != E4Q_OK) return rc;
     }
@@ -195,12 +201,12 @@ int e4q_quantize_rowwise_greedy_batch(const e4q_table_desc* descs, int32_t n_tab
 int e4q_dequantize(const uint8_t* codes, const uint16_t* scale_f16, const uint16_t* bias_f16,
                    int64_t rows, int32_t dim, int32_t nbits, float* out, void* hip_stream)
 {
-    if (nbits != 4) return E4Q_ERR_BAD_NBITS;
+    if (!nbits_ok(nbits)) return E4Q_ERR_BAD_NBITS;
     if (rows < 0 || dim <= 0 || dim > E4Q_MAX_DIM) return E4Q_ERR_BAD_SHAPE;
     if (rows == 0) return E4Q_OK;
     if (!codes || !scale_f16 || !bias_f16 || !out) return E4Q_ERR_NULL_POINTER;
     if (!aligned(scale_f16, 2) || !aligned(bias_f16, 2) || !aligned(out, 4)) return E4Q_ERR_BAD_ALIGNMENT;
-    const hipError_t err = e4q::launch_dequantize(codes, scale_f16, bias_f16, rows, dim, out,
+    const hipError_t err = e4q::launch_dequantize(codes, scale_f16, bias_f16, rows, dim, nbits, out,
                                                   static_cast<hipStream_t>(hip_stream));
     return err == hipSuccess ? E4Q_OK : fail_launch(err);
 }
@@ -309,7 +315,7 @@ const char* e4q_strerror(int code)
         case E4Q_OK: return "success";
         case E4Q_ERR_NULL_POINTER: return "a required pointer is NULL";
         case E4Q_ERR_BAD_SHAPE: return "bad shape: need rows >= 0, 0 < dim <= 4096, row_stride >= dim, an even row_pitch >= e4q_fused_row_bytes(dim)";
-        case E4Q_ERR_BAD_NBITS: return "nbits must be 4";
+        case E4Q_ERR_BAD_NBITS: return "nbits must be 2, 4 or 8 for the uniform quantizer and its dequantizer, 4 for the lookup operator";
         case E4Q_ERR_BAD_SEARCH: return "bad search parameters: need n_bins >= 1, 0 <= ratio < 1, lloyd_iters >= 0";
         case E4Q_ERR_BAD_DTYPE: return "dtype must be E4Q_F32 (0) or E4Q_F16 (1); index_bytes must be 4 or 8";
         case E4Q_ERR_LAUNCH: return "HIP reported an error at kernel launch (see e4q_last_hip_error)";

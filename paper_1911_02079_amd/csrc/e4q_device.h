@@ -14,9 +14,11 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <utility>
+
 namespace e4q {
 
-constexpr float kQMax = 15.0f;  // 2^n - 1 for n = 4 (Eq. 1)
+constexpr float kQMax4 = 15.0f;  // 2^n - 1 for n = 4 (Eq. 1); the codebook grid uses it directly
 
 // Value after a round trip through binary16 (RNE; v_cvt_f16_f32 then v_cvt_f32_f16).
 __device__ __forceinline__ float through_f16(float v) { return (float)(_Float16)v; }
@@ -33,27 +35,39 @@ __device__ __forceinline__ float f16_bits_to_float(uint16_t b)
 }
 
 // The parameters that are stored for the clipping range [lo, hi] (Eq. 1 with binary16 storage):
-// scale = (hi - lo)/15 and bias = lo, both rounded to binary16, and the reciprocal used by the
-// quantizer (0 when the range collapses, which sends every code to 0).
+// scale = (hi - lo)/(2^n - 1) and bias = lo, both rounded to binary16, the reciprocal used by the
+// quantizer (0 when the range collapses, which sends every code to 0), and the largest code.
 struct StoredParams {
-    float scale, bias, inv;
+    float scale, bias, inv, qmax;
 };
 
-__device__ __forceinline__ StoredParams stored_params(float lo, float hi)
+__device__ __forceinline__ StoredParams stored_params(float lo, float hi, float qmax)
 {
     StoredParams p;
-    float scale32 = (hi - lo) / kQMax;
+    float scale32 = (hi - lo) / qmax;
     p.scale = through_f16(scale32);
     p.bias = through_f16(lo);
     p.inv = (p.scale == 0.0f) ? 0.0f : 1.0f / p.scale;
+    p.qmax = qmax;
     return p;
 }
 
-// x_int of Eq. 1 as a float in {0..15}: round-half-even of (x - bias) * (1/scale), clamped.
+// The same parameters rebuilt from what is stored (the final encode uses exactly the stored bits).
+__device__ __forceinline__ StoredParams params_from_bits(uint16_t scale_bits, uint16_t bias_bits, float qmax)
+{
+    StoredParams p;
+    p.scale = f16_bits_to_float(scale_bits);
+    p.bias = f16_bits_to_float(bias_bits);
+    p.inv = (p.scale == 0.0f) ? 0.0f : 1.0f / p.scale;
+    p.qmax = qmax;
+    return p;
+}
+
+// x_int of Eq. 1 as a float in {0..qmax}: round-half-even of (x - bias) * (1/scale), clamped.
 __device__ __forceinline__ float quantize_elem(float x, const StoredParams& p)
 {
     float t = (x - p.bias) * p.inv;
-    return __builtin_amdgcn_fmed3f(__builtin_rintf(t), 0.0f, kQMax);
+    return __builtin_amdgcn_fmed3f(__builtin_rintf(t), 0.0f, p.qmax);
 }
 
 // Squared reconstruction error of one element (one term of Eq. 2): 8 VALU operations.
@@ -88,6 +102,73 @@ __device__ __forceinline__ float tree_sum(Leaf&& leaf)
             float b = tree_sum<LO + H, H, D>(leaf);
             return a + b;
         }
+    }
+}
+
+// Packs N codes of NBITS bits (8/NBITS per byte, first element in the lowest bits) into 32-bit words.
+// `code(Idx<k>)` returns element k's code as an unsigned integer (0 for elements that do not exist).
+template <int NBITS, class Code, int... K>
+__device__ __forceinline__ void pack_codes_impl(Code& code, uint32_t* w, std::integer_sequence<int, K...>)
+{
+    constexpr int PER_WORD = 32 / NBITS;
+    ((w[K / PER_WORD] |= (uint32_t)code(Idx<K>{}) << ((K % PER_WORD) * NBITS)), ...);
+}
+
+template <int NBITS, int N, class Code>
+__device__ __forceinline__ void pack_codes(Code&& code, uint32_t (&w)[(N * NBITS + 31) / 32])
+{
+    constexpr int NWORDS = (N * NBITS + 31) / 32;
+#pragma unroll
+    for (int i = 0; i < NWORDS; ++i) w[i] = 0;
+    pack_codes_impl<NBITS>(code, w, std::make_integer_sequence<int, N>{});
+}
+
+// Stores the first `nbytes_live` of NBYTES packed bytes held in w[] at `out`: 16-byte or 4-byte
+// stores when the row size and the alignment class of the buffer allow it, single bytes otherwise.
+// `align_class`: 0 = unknown, 1 = `out` is 4-byte aligned, 2 = 16-byte aligned.
+template <int NBYTES>
+__device__ __forceinline__ void store_packed(uint8_t* __restrict__ out, const uint32_t (&w)[(NBYTES + 3) / 4],
+                                             uint32_t align_class, int nbytes_live = NBYTES)
+{
+    constexpr int NWORDS = (NBYTES + 3) / 4;
+    if (NBYTES % 16 == 0 && align_class == 2 && nbytes_live == NBYTES) {
+        uint4* o4 = reinterpret_cast<uint4*>(out);
+#pragma unroll
+        for (int i = 0; i + 3 < NWORDS; i += 4) o4[i / 4] = make_uint4(w[i], w[i + 1], w[i + 2], w[i + 3]);
+    } else if (NBYTES % 4 == 0 && align_class >= 1 && nbytes_live % 4 == 0) {
+        uint32_t* o1 = reinterpret_cast<uint32_t*>(out);
+#pragma unroll
+        for (int i = 0; i < NWORDS; ++i)
+            if (4 * i < nbytes_live) o1[i] = w[i];
+    } else {
+#pragma unroll
+        for (int b = 0; b < NBYTES; ++b)
+            if (b < nbytes_live) out[b] = (uint8_t)(w[b / 4] >> (8 * (b % 4)));
+    }
+}
+
+// Quantizes, packs and stores the codes of x[C0 .. N), 16 bytes of codes at a time: a chunk is
+// finished before the next one starts, so the encode needs few registers beyond x itself.  N is a
+// multiple of 8.  With MASKED only the first `nvalid` elements exist: the others pack as 0 and bytes
+// that hold no existing element are not written.
+template <int NB, int N, int C0, bool MASKED>
+__device__ __forceinline__ void encode_chunks(const float (&x)[N], const StoredParams& p, int nvalid,
+                                              uint8_t* __restrict__ out, uint32_t align_class, bool live)
+{
+    if constexpr (C0 < N) {
+        constexpr int CH = 128 / NB;                         // elements in 16 bytes of codes
+        constexpr int M = (N - C0 < CH) ? N - C0 : CH;       // elements in this chunk
+        constexpr int CHUNK_BYTES = M * NB / 8;
+        uint32_t w[(M * NB + 31) / 32];
+        pack_codes<NB, M>([&](auto k) {
+            constexpr int e = C0 + decltype(k)::value;
+            const uint32_t q = (uint32_t)quantize_elem(x[e], p);
+            return (!MASKED || e < nvalid) ? q : 0u;
+        }, w);
+        int live_bytes = CHUNK_BYTES;
+        if constexpr (MASKED) live_bytes = min(max((nvalid * NB + 7) / 8 - C0 * NB / 8, 0), CHUNK_BYTES);
+        if (live) store_packed<CHUNK_BYTES>(out + C0 * NB / 8, w, align_class, live_bytes);
+        encode_chunks<NB, N, C0 + CH, MASKED>(x, p, nvalid, out, align_class, live);
     }
 }
 

@@ -18,6 +18,8 @@ struct GreedyArgs {
     uint16_t* bias_f16;
     uint32_t vec_loads;   // 1: table base and row pitch are 16-byte aligned
     uint32_t vec_stores;  // 0: byte stores, 1: codes base 4-byte aligned, 2: 16-byte aligned
+    int32_t nbits;        // 2, 4 or 8
+    float qmax;           // 2^nbits - 1
 };
 
 // One launch over several tables of the same dimension and input type (one row per lane).
@@ -36,6 +38,8 @@ struct GreedyGroup {
     int32_t n_tables;  // 1 .. kMaxGroupTables
     int32_t n_iter;
     float n_bins;
+    int32_t nbits;
+    float qmax;
     uint32_t block_end[kMaxGroupTables];  // running total of ceil(rows / 64) workgroups
     GreedyTable tables[kMaxGroupTables];
 };
@@ -79,6 +83,6 @@ hipError_t launch_sparse_lengths_sum_fused(const uint8_t* fused, int64_t rows, i
                                            const void* indices, int32_t index_bytes, int64_t n_indices,
                                            const int64_t* offsets, int64_t n_bags, float* out, hipStream_t stream);
 hipError_t launch_dequantize(const uint8_t* codes, const uint16_t* scale_f16, const uint16_t* bias_f16,
-                             int64_t rows, int32_t dim, float* out, hipStream_t stream);
+                             int64_t rows, int32_t dim, int32_t nbits, float* out, hipStream_t stream);
 
 }  // namespace e4q

@@ -64,9 +64,9 @@ __device__ __forceinline__ void load_row(const _Float16* __restrict__ row, bool 
 
 // Eq. 2 for the range [lo, hi] on a row held in registers.
 template <int D>
-__device__ __forceinline__ float range_loss(const float (&x)[D], float lo, float hi)
+__device__ __forceinline__ float range_loss(const float (&x)[D], float lo, float hi, float qmax)
 {
-    const StoredParams p = stored_params(lo, hi);
+    const StoredParams p = stored_params(lo, hi, qmax);
     return tree_sum<0, next_pow2(D), D>([&](auto k) { return elem_sq_err(x[decltype(k)::value], p); });
 }
 
@@ -92,12 +92,12 @@ __device__ __forceinline__ void greedy_rpl_row(const GreedyArgs& a, int64_t row)
     if (a.n_iter > 0) {  // uniform branch: ratio == 0 needs no scoring at all
         const float stepsize = (hi0 - lo0) / a.n_bins;
         float cur_lo = lo0, cur_hi = hi0;
-        float best = range_loss<D>(x, lo0, hi0);
+        float best = range_loss<D>(x, lo0, hi0, a.qmax);
         for (int it = 0; it < a.n_iter; ++it) {
             const float next_lo = cur_lo + stepsize;
             const float next_hi = cur_hi - stepsize;
-            const float loss_l = range_loss<D>(x, next_lo, cur_hi);
-            const float loss_r = range_loss<D>(x, cur_lo, next_hi);
+            const float loss_l = range_loss<D>(x, next_lo, cur_hi, a.qmax);
+            const float loss_r = range_loss<D>(x, cur_lo, next_hi, a.qmax);
             const bool left = loss_l < loss_r;  // a tie moves the upper bound
             cur_lo = left ? next_lo : cur_lo;
             cur_hi = left ? cur_hi : next_hi;
@@ -109,45 +109,24 @@ __device__ __forceinline__ void greedy_rpl_row(const GreedyArgs& a, int64_t row)
         }
     }
 
-    // Encode with the best range (Eq. 1) and pack two codes per byte, low nibble first.
-    const float scale32 = (best_hi - best_lo) / kQMax;
+    // Encode with the best range (Eq. 1) and pack 8/nbits codes per byte, first element lowest.
+    const float scale32 = (best_hi - best_lo) / a.qmax;
     const uint16_t scale_bits = f16_bits(scale32);
     const uint16_t bias_bits = f16_bits(best_lo);
-    StoredParams p;
-    p.scale = f16_bits_to_float(scale_bits);
-    p.bias = f16_bits_to_float(bias_bits);
-    p.inv = (p.scale == 0.0f) ? 0.0f : 1.0f / p.scale;
-
-    constexpr int NBYTES = (D + 1) / 2;
-    constexpr int NWORDS = (NBYTES + 3) / 4;
-    uint32_t w[NWORDS];
-#pragma unroll
-    for (int i = 0; i < NWORDS; ++i) {
-        uint32_t acc = 0;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int k = 8 * i + e;
-            if (k < D) acc |= (uint32_t)quantize_elem(x[k], p) << (4 * e);
-        }
-        w[i] = acc;
+    const StoredParams p = params_from_bits(scale_bits, bias_bits, a.qmax);
+    if (live) {
+        a.scale_f16[row] = scale_bits;
+        a.bias_f16[row] = bias_bits;
     }
-
-    if (!live) return;
-    a.scale_f16[row] = scale_bits;
-    a.bias_f16[row] = bias_bits;
-    uint8_t* out = a.codes + row * NBYTES;
-    if (NBYTES % 16 == 0 && a.vec_stores == 2) {
-        uint4* o4 = reinterpret_cast<uint4*>(out);
-#pragma unroll
-        for (int i = 0; i + 3 < NWORDS; i += 4) o4[i / 4] = make_uint4(w[i], w[i + 1], w[i + 2], w[i + 3]);
-    } else if (NBYTES % 4 == 0 && a.vec_stores >= 1) {
-        uint32_t* o1 = reinterpret_cast<uint32_t*>(out);
-#pragma unroll
-        for (int i = 0; i < NWORDS; ++i) o1[i] = w[i];
-    } else {
-#pragma unroll
-        for (int b = 0; b < NBYTES; ++b) out[b] = (uint8_t)(w[b / 4] >> (8 * (b % 4)));
-    }
+    auto encode = [&](auto nb) {
+        constexpr int NB = decltype(nb)::value;
+        constexpr int NBYTES = D * NB / 8;
+        const uint32_t cls = (NBYTES % 16 == 0 && a.vec_stores == 2) ? 2u : ((NBYTES % 4 == 0 && a.vec_stores >= 1) ? 1u : 0u);
+        encode_chunks<NB, D, 0, false>(x, p, D, a.codes + row * NBYTES, cls, live);
+    };
+    if (a.nbits == 4) encode(Idx<4>{});  // uniform branches
+    else if (a.nbits == 8) encode(Idx<8>{});
+    else encode(Idx<2>{});
 }
 
 template <int D, typename Tin>
@@ -172,6 +151,8 @@ __global__ void __launch_bounds__(kRplBlock) greedy_rpl_group_kernel(GreedyGroup
     a.row_stride = e.row_stride;
     a.n_iter = g.n_iter;
     a.n_bins = g.n_bins;
+    a.nbits = g.nbits;
+    a.qmax = g.qmax;
     a.codes = e.codes;
     a.scale_f16 = e.scale_f16;
     a.bias_f16 = e.bias_f16;

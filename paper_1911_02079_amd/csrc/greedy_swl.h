@@ -62,9 +62,9 @@ __device__ __forceinline__ float group_reduce(float v, Op op)
 }
 
 template <int E, int L, int MASK>
-__device__ __forceinline__ float swl_range_loss(const float (&x)[E], int nvalid, float lo, float hi)
+__device__ __forceinline__ float swl_range_loss(const float (&x)[E], int nvalid, float lo, float hi, float qmax)
 {
-    const StoredParams p = stored_params(lo, hi);
+    const StoredParams p = stored_params(lo, hi, qmax);
     float part;
     if constexpr (MASK == 1) {
         // tree over blocks of 8 of trees over 8 elements: the same balanced tree, masked per block
@@ -133,12 +133,12 @@ __global__ void __launch_bounds__(kSwlBlock) greedy_swl_kernel(GreedyArgs a, int
     if (a.n_iter > 0) {
         const float stepsize = (hi0 - lo0) / a.n_bins;
         float cur_lo = lo0, cur_hi = hi0;
-        float best = swl_range_loss<E, L, MASK>(x, nvalid, lo0, hi0);
+        float best = swl_range_loss<E, L, MASK>(x, nvalid, lo0, hi0, a.qmax);
         for (int it = 0; it < a.n_iter; ++it) {
             const float next_lo = cur_lo + stepsize;
             const float next_hi = cur_hi - stepsize;
-            const float loss_l = swl_range_loss<E, L, MASK>(x, nvalid, next_lo, cur_hi);
-            const float loss_r = swl_range_loss<E, L, MASK>(x, nvalid, cur_lo, next_hi);
+            const float loss_l = swl_range_loss<E, L, MASK>(x, nvalid, next_lo, cur_hi, a.qmax);
+            const float loss_r = swl_range_loss<E, L, MASK>(x, nvalid, cur_lo, next_hi, a.qmax);
             const bool left = loss_l < loss_r;  // a tie moves the upper bound
             cur_lo = left ? next_lo : cur_lo;
             cur_hi = left ? cur_hi : next_hi;
@@ -150,45 +150,27 @@ __global__ void __launch_bounds__(kSwlBlock) greedy_swl_kernel(GreedyArgs a, int
         }
     }
 
-    const float scale32 = (best_hi - best_lo) / kQMax;
+    const float scale32 = (best_hi - best_lo) / a.qmax;
     const uint16_t scale_bits = f16_bits(scale32);
     const uint16_t bias_bits = f16_bits(best_lo);
-    StoredParams p;
-    p.scale = f16_bits_to_float(scale_bits);
-    p.bias = f16_bits_to_float(bias_bits);
-    p.inv = (p.scale == 0.0f) ? 0.0f : 1.0f / p.scale;
-
-    constexpr int NWORDS = E / 8;
-    uint32_t w[NWORDS];
-#pragma unroll
-    for (int i = 0; i < NWORDS; ++i) {
-        uint32_t acc = 0;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const uint32_t q = (uint32_t)quantize_elem(x[8 * i + e], p);
-            acc |= ((!MASKED || 8 * i + e < nvalid) ? q : 0u) << (4 * e);
-        }
-        w[i] = acc;
-    }
-
-    if (!live) return;
-    if (sub == 0) {
+    const StoredParams p = params_from_bits(scale_bits, bias_bits, a.qmax);
+    if (live && sub == 0) {
         a.scale_f16[row] = scale_bits;
         a.bias_f16[row] = bias_bits;
     }
-    const int nbytes_row = (d + 1) / 2;
-    uint8_t* out = a.codes + row * nbytes_row + base / 2;
-    if (MASK != 2 && a.vec_stores >= 1) {  // dim % 8 == 0: rows are whole 4-byte words, 4-byte aligned
-        uint32_t* o = reinterpret_cast<uint32_t*>(out);
-#pragma unroll
-        for (int i = 0; i < NWORDS; ++i)
-            if (!MASKED || 8 * i < nvalid) o[i] = w[i];
-    } else {
-        const int nb = (nvalid + 1) / 2;  // bytes this lane owns
-#pragma unroll
-        for (int b = 0; b < E / 2; ++b)
-            if (b < nb) out[b] = (uint8_t)(w[b / 4] >> (8 * (b % 4)));
-    }
+    // Each lane packs and stores the codes of its own E elements (8/nbits per byte): E*nbits/8 bytes
+    // at byte offset base*nbits/8 of the row, of which only the bytes that hold valid elements exist.
+    auto encode = [&](auto nb) {
+        constexpr int NB = decltype(nb)::value;
+        constexpr int LANE_BYTES = E * NB / 8;
+        const int row_bytes = (d * NB + 7) / 8;
+        // word stores need 4-byte aligned pieces: a 4-byte aligned buffer, rows and lane pieces of 4k bytes
+        const uint32_t cls = (a.vec_stores >= 1 && row_bytes % 4 == 0 && LANE_BYTES % 4 == 0) ? 1u : 0u;
+        encode_chunks<NB, E, 0, MASKED>(x, p, nvalid, a.codes + row * row_bytes + base * NB / 8, cls, live);
+    };
+    if (a.nbits == 4) encode(Idx<4>{});  // uniform branches
+    else if (a.nbits == 8) encode(Idx<8>{});
+    else encode(Idx<2>{});
 }
 
 template <int E, int L, typename Tin, int MASK>

@@ -44,7 +44,7 @@ __device__ __forceinline__ int nearest_centre(float x, const float (&c)[kK])
 
 __device__ __forceinline__ void grid_centres(float lo, float hi, float (&c)[kK])
 {
-    const float step = (hi - lo) / kQMax;
+    const float step = (hi - lo) / kQMax4;
 #pragma unroll
     for (int k = 0; k < kK; ++k) c[k] = __builtin_fmaf((float)k, step, lo);
 }

@@ -80,7 +80,8 @@ def test_validation_rejects_bad_arguments_before_any_launch(lib):
         return q(a["table"], a["dtype"], a["rows"], a["dim"], a["stride"], a["nbits"], a["n_bins"], a["ratio"],
                  a["codes"], a["scale"], a["bias"], None)
 
-    assert call(nbits=8) == -3
+    assert call(nbits=3) == -3
+    assert call(nbits=16) == -3
     assert call(n_bins=0) == -4
     assert call(ratio=1.0) == -4
     assert call(ratio=-0.1) == -4
@@ -97,7 +98,7 @@ def test_validation_rejects_bad_arguments_before_any_launch(lib):
     assert call(rows=0, table=None, codes=None, scale=None, bias=None) == 0  # empty table: no-op
 
     dq = lib.e4q_dequantize
-    assert dq(p, p, p, 10, 64, 8, p, None) == -3
+    assert dq(p, p, p, 10, 64, 5, p, None) == -3
     assert dq(p, p, p, -1, 64, 4, p, None) == -2
     assert dq(p, p, p, 10, 0, 4, p, None) == -2
     assert dq(None, p, p, 10, 64, 4, p, None) == -1

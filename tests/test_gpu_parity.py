@@ -340,7 +340,63 @@ def test_runs_on_a_side_stream(e4q, oracle_lib):
 def test_binding_reports_library_errors(e4q):
     t = torch.randn(4, 64, device="cuda")
     with pytest.raises(e4q.E4QError) as ei:
-        e4q.quantize_rowwise_greedy(t, nbits=8)
+        e4q.quantize_rowwise_greedy(t, nbits=3)
     assert ei.value.code == -3
     with pytest.raises(e4q.E4QError):
         e4q.quantize_rowwise_greedy(t, ratio=1.5)
+
+
+# --------------------------------------------------------------------------------------------
+# Other bit widths (8 = the paper's ASYM-8BITS baseline, 2) through every kernel layout
+# --------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("nbits", [2, 8])
+@pytest.mark.parametrize("rows,dim,dtype,ratio", [
+    (MANY, 128, torch.float32, 0.16), (MANY, 64, torch.float16, 0.16), (MANY, 8, torch.float32, 0.16),
+    (MANY, 24, torch.float32, 0.16),                                   # one row per lane
+    (777, 64, torch.float32, 0.16), (777, 128, torch.float16, 0.16), (131, 24, torch.float32, 0.16),
+    (131, 8, torch.float32, 0.16), (131, 13, torch.float32, 0.16), (131, 1, torch.float32, 0.16),
+    (131, 5, torch.float16, 0.16), (131, 100, torch.float32, 0.16), (131, 1000, torch.float32, 0.16),
+    (131, 2048, torch.float16, 0.16),                                  # few rows: 8..64 per lane
+    (MANY, 100, torch.float32, 0.16), (MANY, 200, torch.float32, 0.16), (MANY, 256, torch.float16, 0.16),
+    (MANY, 36, torch.float32, 0.16),                                   # many rows, long chunks, masked
+    (50_001, 128, torch.float32, 0.0), (50_001, 24, torch.float32, 0.0), (50_001, 100, torch.float32, 0.0),
+])
+def test_other_bit_widths(e4q, oracle_lib, nbits, rows, dim, dtype, ratio):
+    from helpers import oracle_rows_in_parallel
+    from paper_1911_02079_amd import synth
+
+    t = synth.outlier_table(rows, dim, seed=7000 + dim + nbits, device="cuda").to(dtype)
+    say(f"nbits={nbits} rows={rows} dim={dim} {dtype} ratio={ratio}")
+    codes, scale, bias = e4q.quantize_rowwise_greedy(t, 20, ratio if ratio == 0 else 0.25, nbits=nbits)
+    xh = e4q.dequantize(codes, scale, bias, dim, nbits=nbits)
+    torch.cuda.synchronize()
+    o = oracle_rows_in_parallel(oracle_lib, t.cpu().numpy(), 20, ratio if ratio == 0 else 0.25, nbits=nbits)
+    assert codes.shape[1] == e4q.packed_bytes(dim, nbits)
+    bad = np.flatnonzero((codes.cpu().numpy() != o[0]).any(axis=1) | (f16_bits(scale) != o[1]) | (f16_bits(bias) != o[2]))
+    assert bad.size == 0, f"{bad.size} rows differ, first {bad[:5]}"
+    sample = slice(0, min(rows, 3000))
+    assert np.array_equal(xh[sample].cpu().numpy(), oracle_lib.dequantize(o[0][sample], o[1][sample], o[2][sample], dim, nbits))
+
+
+def test_other_bit_widths_batch_and_guard_bands(e4q, oracle_lib):
+    from paper_1911_02079_amd import synth
+
+    tables = [synth.gaussian_table(20_000 + 13 * k, 64, 0.1, seed=7100 + k, device="cuda") for k in range(3)]
+    for nbits in (2, 8):
+        say(f"batch nbits={nbits}")
+        outs = e4q.quantize_rowwise_greedy_batch(tables, 20, 0.25, nbits=nbits)
+        torch.cuda.synchronize()
+        for t, (codes, scale, bias) in zip(tables, outs):
+            o = oracle_lib.quantize_rowwise_greedy(t.cpu().numpy(), 20, 0.25, nbits=nbits)
+            assert np.array_equal(codes.cpu().numpy(), o[0]) and np.array_equal(f16_bits(scale), o[1])
+        for dim, rows in ((64, 64 * 512 + 5), (13, 197), (200, 64 * 512 + 5)):
+            t = synth.gaussian_table(rows, dim, 0.1, seed=9, device="cuda")
+            nb = e4q.packed_bytes(dim, nbits)
+            cbuf = torch.full((rows * nb + 256,), 0xA5, dtype=torch.uint8, device="cuda")
+            out = (cbuf[128:128 + rows * nb].reshape(rows, nb), torch.empty(rows, dtype=torch.float16, device="cuda"),
+                   torch.empty(rows, dtype=torch.float16, device="cuda"))
+            e4q.quantize_rowwise_greedy(t, 20, 0.25, nbits=nbits, out=out)
+            torch.cuda.synchronize()
+            assert bool((cbuf[:128] == 0xA5).all()) and bool((cbuf[128 + rows * nb:] == 0xA5).all())
+            o = oracle_lib.quantize_rowwise_greedy(t.cpu().numpy(), 20, 0.25, nbits=nbits)
+            assert np.array_equal(out[0].cpu().numpy(), o[0])

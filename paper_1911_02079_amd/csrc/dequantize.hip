@@ -12,30 +12,32 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 // dim % 4 == 0, codes aligned to the 4-element group (NBITS/2 bytes), out 16-byte aligned.  One
 // thread per 4 elements: a wave reads contiguous code bytes and writes 1 KiB of contiguous output
 // per store instruction (full cache lines, so nothing is written twice).
-template <int NBITS>
+template <int NBITS, bool WIDE>
 __global__ void __launch_bounds__(kDqBlock) dequantize_w4_kernel(const void* __restrict__ codes,
                                                                 const uint16_t* __restrict__ scale_f16,
                                                                 const uint16_t* __restrict__ bias_f16,
                                                                 int64_t n_quads, uint32_t quads_per_row,
                                                                 floatx4* __restrict__ out)
 {
-    const int64_t stride = (int64_t)gridDim.x * kDqBlock;
-    for (int64_t w = (int64_t)blockIdx.x * kDqBlock + threadIdx.x; w < n_quads; w += stride) {
-        const int64_t row = (n_quads <= 0xffffffffLL) ? (int64_t)((uint32_t)w / quads_per_row) : w / quads_per_row;
-        const float scale = f16_bits_to_float(scale_f16[row]);
-        const float bias = f16_bits_to_float(bias_f16[row]);
-        uint32_t c;  // the four codes of this thread, NBITS each, first element lowest
-        if constexpr (NBITS == 8) c = __builtin_nontemporal_load(static_cast<const uint32_t*>(codes) + w);
-        else if constexpr (NBITS == 4) c = __builtin_nontemporal_load(static_cast<const uint16_t*>(codes) + w);
-        else c = __builtin_nontemporal_load(static_cast<const uint8_t*>(codes) + w);
-        constexpr uint32_t kMask = (1u << NBITS) - 1u;
-        floatx4 v;
-        v.x = __builtin_fmaf((float)(c & kMask), scale, bias);
-        v.y = __builtin_fmaf((float)((c >> NBITS) & kMask), scale, bias);
-        v.z = __builtin_fmaf((float)((c >> (2 * NBITS)) & kMask), scale, bias);
-        v.w = __builtin_fmaf((float)((c >> (3 * NBITS)) & kMask), scale, bias);
-        __builtin_nontemporal_store(v, out + w);
-    }
+    // One group of four elements per thread and no loop: neighbouring workgroups write neighbouring
+    // memory (measured 20 % faster than a capped grid with a grid-stride loop).  WIDE selects
+    // 64-bit index arithmetic for tables with 2^32 or more groups.
+    const int64_t w = (int64_t)blockIdx.x * kDqBlock + threadIdx.x;
+    if (w >= n_quads) return;
+    const int64_t row = WIDE ? w / quads_per_row : (int64_t)((uint32_t)w / quads_per_row);
+    const float scale = f16_bits_to_float(scale_f16[row]);
+    const float bias = f16_bits_to_float(bias_f16[row]);
+    uint32_t c;  // the four codes of this thread, NBITS each, first element lowest
+    if constexpr (NBITS == 8) c = __builtin_nontemporal_load(static_cast<const uint32_t*>(codes) + w);
+    else if constexpr (NBITS == 4) c = __builtin_nontemporal_load(static_cast<const uint16_t*>(codes) + w);
+    else c = __builtin_nontemporal_load(static_cast<const uint8_t*>(codes) + w);
+    constexpr uint32_t kMask = (1u << NBITS) - 1u;
+    floatx4 v;
+    v.x = __builtin_fmaf((float)(c & kMask), scale, bias);
+    v.y = __builtin_fmaf((float)((c >> NBITS) & kMask), scale, bias);
+    v.z = __builtin_fmaf((float)((c >> (2 * NBITS)) & kMask), scale, bias);
+    v.w = __builtin_fmaf((float)((c >> (3 * NBITS)) & kMask), scale, bias);
+    __builtin_nontemporal_store(v, out + w);
 }
 
 // Any dim and alignment.  One thread per output element.
@@ -58,32 +60,37 @@ __global__ void __launch_bounds__(kDqBlock) dequantize_any_kernel(const uint8_t*
     }
 }
 
+template <int NBITS>
+static void launch_w4(const void* codes, const uint16_t* scale_f16, const uint16_t* bias_f16, int64_t n_quads,
+                      uint32_t quads_per_row, floatx4* out, hipStream_t stream)
+{
+    const dim3 grid((unsigned)((n_quads + kDqBlock - 1) / kDqBlock)), block(kDqBlock);
+    if (n_quads > 0xffffffffLL)
+        hipLaunchKernelGGL((dequantize_w4_kernel<NBITS, true>), grid, block, 0, stream, codes, scale_f16, bias_f16,
+                           n_quads, quads_per_row, out);
+    else
+        hipLaunchKernelGGL((dequantize_w4_kernel<NBITS, false>), grid, block, 0, stream, codes, scale_f16, bias_f16,
+                           n_quads, quads_per_row, out);
+}
+
 hipError_t launch_dequantize(const uint8_t* codes, const uint16_t* scale_f16, const uint16_t* bias_f16,
                              int64_t rows, int32_t dim, int32_t nbits, float* out, hipStream_t stream)
 {
-    // One item per thread: neighbouring workgroups then write neighbouring memory, which measured 20 %
-    // faster than a capped grid with a grid-stride loop (the loop remains for > 2^31 workgroups).
-    const int64_t max_blocks = 0x7fffffffLL;
     const uintptr_t group_bytes = nbits == 8 ? 4 : (nbits == 4 ? 2 : 1);
+    const int64_t n_quads = rows * (dim / 4);
     const bool fast = dim % 4 == 0 && (reinterpret_cast<uintptr_t>(codes) % group_bytes == 0) &&
-                      (reinterpret_cast<uintptr_t>(out) % 16 == 0);
+                      (reinterpret_cast<uintptr_t>(out) % 16 == 0) &&
+                      (n_quads + kDqBlock - 1) / kDqBlock <= 0x7fffffffLL;
     if (fast) {
-        const int64_t n_quads = rows * (dim / 4);
-        int64_t blocks = (n_quads + kDqBlock - 1) / kDqBlock;
-        if (blocks > max_blocks) blocks = max_blocks;
-        const dim3 grid((unsigned)blocks), block(kDqBlock);
         floatx4* o4 = reinterpret_cast<floatx4*>(out);
         const uint32_t qpr = (uint32_t)(dim / 4);
-        if (nbits == 8)
-            hipLaunchKernelGGL(dequantize_w4_kernel<8>, grid, block, 0, stream, codes, scale_f16, bias_f16, n_quads, qpr, o4);
-        else if (nbits == 4)
-            hipLaunchKernelGGL(dequantize_w4_kernel<4>, grid, block, 0, stream, codes, scale_f16, bias_f16, n_quads, qpr, o4);
-        else
-            hipLaunchKernelGGL(dequantize_w4_kernel<2>, grid, block, 0, stream, codes, scale_f16, bias_f16, n_quads, qpr, o4);
+        if (nbits == 8) launch_w4<8>(codes, scale_f16, bias_f16, n_quads, qpr, o4, stream);
+        else if (nbits == 4) launch_w4<4>(codes, scale_f16, bias_f16, n_quads, qpr, o4, stream);
+        else launch_w4<2>(codes, scale_f16, bias_f16, n_quads, qpr, o4, stream);
     } else {
         const int64_t n_elems = rows * dim;
         int64_t blocks = (n_elems + kDqBlock - 1) / kDqBlock;
-        if (blocks > max_blocks) blocks = max_blocks;
+        if (blocks > 0x7fffffffLL) blocks = 0x7fffffffLL;  // the kernel loops over what is left
         hipLaunchKernelGGL(dequantize_any_kernel, dim3((unsigned)blocks), dim3(kDqBlock), 0, stream, codes,
                            scale_f16, bias_f16, n_elems, (uint32_t)dim, (uint32_t)nbits, out);
     }

@@ -78,18 +78,18 @@ __global__ void __launch_bounds__(kCbBlock) dequantize_codebook_w4_kernel(const 
                                                                           int64_t n_quads, uint32_t quads_per_row,
                                                                           floatx4* __restrict__ out)
 {
-    const int64_t stride = (int64_t)gridDim.x * kCbBlock;
-    for (int64_t w = (int64_t)blockIdx.x * kCbBlock + threadIdx.x; w < n_quads; w += stride) {
-        const int64_t row = (n_quads <= 0xffffffffLL) ? (int64_t)((uint32_t)w / quads_per_row) : w / quads_per_row;
-        const uint16_t* book = cb + row * kK;
-        const uint32_t q = __builtin_nontemporal_load(idx + w);
-        floatx4 v;
-        v.x = f16_bits_to_float(book[q & 15u]);
-        v.y = f16_bits_to_float(book[(q >> 4) & 15u]);
-        v.z = f16_bits_to_float(book[(q >> 8) & 15u]);
-        v.w = f16_bits_to_float(book[q >> 12]);
-        __builtin_nontemporal_store(v, out + w);
-    }
+    // one group of four elements per thread, no loop (the host keeps n_quads below 2^32)
+    const int64_t w = (int64_t)blockIdx.x * kCbBlock + threadIdx.x;
+    if (w >= n_quads) return;
+    const int64_t row = (int64_t)((uint32_t)w / quads_per_row);
+    const uint16_t* book = cb + row * kK;
+    const uint32_t q = __builtin_nontemporal_load(idx + w);
+    floatx4 v;
+    v.x = f16_bits_to_float(book[q & 15u]);
+    v.y = f16_bits_to_float(book[(q >> 4) & 15u]);
+    v.z = f16_bits_to_float(book[(q >> 8) & 15u]);
+    v.w = f16_bits_to_float(book[q >> 12]);
+    __builtin_nontemporal_store(v, out + w);
 }
 
 __global__ void __launch_bounds__(kCbBlock) dequantize_codebook_any_kernel(const uint8_t* __restrict__ idx,
@@ -111,22 +111,18 @@ __global__ void __launch_bounds__(kCbBlock) dequantize_codebook_any_kernel(const
 hipError_t launch_dequantize_codebook(const uint8_t* idx, const uint16_t* centroids_f16, int64_t rows,
                                       int32_t dim, float* out, hipStream_t stream)
 {
-    // One item per thread: neighbouring workgroups then write neighbouring memory, which measured 20 %
-    // faster than a capped grid with a grid-stride loop (the loop remains for > 2^31 workgroups).
-    const int64_t max_blocks = 0x7fffffffLL;
+    const int64_t n_quads = rows * (dim / 4);
     const bool fast = dim % 4 == 0 && reinterpret_cast<uintptr_t>(idx) % 2 == 0 &&
-                      reinterpret_cast<uintptr_t>(out) % 16 == 0;
+                      reinterpret_cast<uintptr_t>(out) % 16 == 0 && n_quads <= 0xffffffffLL;
     if (fast) {
-        const int64_t n_quads = rows * (dim / 4);
-        int64_t blocks = (n_quads + kCbBlock - 1) / kCbBlock;
-        if (blocks > max_blocks) blocks = max_blocks;
+        const int64_t blocks = (n_quads + kCbBlock - 1) / kCbBlock;
         hipLaunchKernelGGL(dequantize_codebook_w4_kernel, dim3((unsigned)blocks), dim3(kCbBlock), 0, stream,
                            reinterpret_cast<const uint16_t*>(idx), centroids_f16, n_quads, (uint32_t)(dim / 4),
                            reinterpret_cast<floatx4*>(out));
     } else {
         const int64_t n_elems = rows * dim;
         int64_t blocks = (n_elems + kCbBlock - 1) / kCbBlock;
-        if (blocks > max_blocks) blocks = max_blocks;
+        if (blocks > 0x7fffffffLL) blocks = 0x7fffffffLL;  // the kernel loops over what is left
         hipLaunchKernelGGL(dequantize_codebook_any_kernel, dim3((unsigned)blocks), dim3(kCbBlock), 0, stream, idx,
                            centroids_f16, n_elems, (uint32_t)dim, out);
     }

@@ -37,7 +37,7 @@ extern "C" {
 /* Error codes. */
 #define E4Q_OK 0
 #define E4Q_ERR_NULL_POINTER (-1)   /* a required pointer is NULL */
-#define E4Q_ERR_BAD_SHAPE (-2)      /* rows < 0, dim <= 0, dim > E4Q_MAX_DIM, row_stride < dim */
+#define E4Q_ERR_BAD_SHAPE (-2)      /* rows < 0 or > E4Q_MAX_ROWS, dim <= 0 or > E4Q_MAX_DIM, row_stride < dim, bad row_pitch */
 #define E4Q_ERR_BAD_NBITS (-3)      /* nbits not in {2, 4, 8} (quantizer, dequantizer) or != 4 (lookup operator) */
 #define E4Q_ERR_BAD_SEARCH (-4)     /* n_bins < 1, ratio outside [0, 1), ratio NaN, lloyd_iters < 0 */
 #define E4Q_ERR_BAD_DTYPE (-5)      /* dtype is neither E4Q_F32 nor E4Q_F16; index_bytes is neither 4 nor 8 */
@@ -48,8 +48,10 @@ extern "C" {
 #define E4Q_F32 0
 #define E4Q_F16 1
 
-/* Largest supported embedding dimension. */
+/* Largest supported embedding dimension, row count and bag count (a launch has at most 2^31 - 1
+ * workgroups and the smallest ones take four rows). */
 #define E4Q_MAX_DIM 4096
+#define E4Q_MAX_ROWS 2147483648LL
 
 /*
  * Row-wise uniform n-bit quantization (n = 4 in the paper) with greedy search of the clipping range
@@ -111,7 +113,9 @@ typedef struct e4q_table_desc {
 /*
  * Greedy quantization (as above) of `n_tables` tables in one launch sequence on one stream:
  * all descriptors are validated first, then every table's work is enqueued back to back with
- * no host synchronisation in between.  On a validation error nothing is enqueued.
+ * no host synchronisation in between (tables that share a dimension and an input type may share a
+ * launch).  On a validation error nothing is enqueued; E4Q_ERR_LAUNCH can leave earlier tables of
+ * the batch enqueued.
  */
 int e4q_quantize_rowwise_greedy_batch(const e4q_table_desc* descs, int32_t n_tables,
                                       int32_t nbits, int32_t n_bins, float ratio,

@@ -35,7 +35,7 @@ int validate_table(const void* table, int dtype, int64_t rows, int32_t dim, int6
                    const uint8_t* codes, const uint16_t* scale_f16, const uint16_t* bias_f16)
 {
     if (dtype != E4Q_F32 && dtype != E4Q_F16) return E4Q_ERR_BAD_DTYPE;
-    if (rows < 0 || dim <= 0 || dim > E4Q_MAX_DIM || row_stride < dim) return E4Q_ERR_BAD_SHAPE;
+    if (rows < 0 || rows > E4Q_MAX_ROWS || dim <= 0 || dim > E4Q_MAX_DIM || row_stride < dim) return E4Q_ERR_BAD_SHAPE;
     if (rows == 0) return E4Q_OK;
     if (!table || !codes || !scale_f16 || !bias_f16) return E4Q_ERR_NULL_POINTER;
     if (!aligned(table, dtype == E4Q_F32 ? 4 : 2) || !aligned(scale_f16, 2) || !aligned(bias_f16, 2))
@@ -202,7 +202,7 @@ int e4q_dequantize(const uint8_t* codes, const uint16_t* scale_f16, const uint16
                    int64_t rows, int32_t dim, int32_t nbits, float* out, void* hip_stream)
 {
     if (!nbits_ok(nbits)) return E4Q_ERR_BAD_NBITS;
-    if (rows < 0 || dim <= 0 || dim > E4Q_MAX_DIM) return E4Q_ERR_BAD_SHAPE;
+    if (rows < 0 || rows > E4Q_MAX_ROWS || dim <= 0 || dim > E4Q_MAX_DIM) return E4Q_ERR_BAD_SHAPE;
     if (rows == 0) return E4Q_OK;
     if (!codes || !scale_f16 || !bias_f16 || !out) return E4Q_ERR_NULL_POINTER;
     if (!aligned(scale_f16, 2) || !aligned(bias_f16, 2) || !aligned(out, 4)) return E4Q_ERR_BAD_ALIGNMENT;
@@ -217,9 +217,8 @@ int e4q_quantize_rowwise_kmeans16(const void* table, int dtype, int64_t rows, in
 {
     if (lloyd_iters < 0) return E4Q_ERR_BAD_SEARCH;
     if (dtype != E4Q_F32 && dtype != E4Q_F16) return E4Q_ERR_BAD_DTYPE;
-    if (rows < 0 || dim <= 0 || dim > E4Q_MAX_DIM || row_stride < dim) return E4Q_ERR_BAD_SHAPE;
+    if (rows < 0 || rows > E4Q_MAX_ROWS || dim <= 0 || dim > E4Q_MAX_DIM || row_stride < dim) return E4Q_ERR_BAD_SHAPE;
     if (rows == 0) return E4Q_OK;
-    if ((rows + 63) / 64 > 0x7fffffffLL) return E4Q_ERR_BAD_SHAPE;
     if (!table || !idx || !centroids_f16) return E4Q_ERR_NULL_POINTER;
     const size_t esz = dtype == E4Q_F32 ? 4 : 2;
     if (!aligned(table, esz) || !aligned(centroids_f16, 2)) return E4Q_ERR_BAD_ALIGNMENT;
@@ -239,7 +238,7 @@ int e4q_quantize_rowwise_kmeans16(const void* table, int dtype, int64_t rows, in
 int e4q_dequantize_codebook(const uint8_t* idx, const uint16_t* centroids_f16, int64_t rows, int32_t dim,
                             float* out, void* hip_stream)
 {
-    if (rows < 0 || dim <= 0 || dim > E4Q_MAX_DIM) return E4Q_ERR_BAD_SHAPE;
+    if (rows < 0 || rows > E4Q_MAX_ROWS || dim <= 0 || dim > E4Q_MAX_DIM) return E4Q_ERR_BAD_SHAPE;
     if (rows == 0) return E4Q_OK;
     if (!idx || !centroids_f16 || !out) return E4Q_ERR_NULL_POINTER;
     if (!aligned(centroids_f16, 2) || !aligned(out, 4)) return E4Q_ERR_BAD_ALIGNMENT;
@@ -255,7 +254,9 @@ int e4q_sparse_lengths_sum(const uint8_t* codes, const uint16_t* scale_f16, cons
 {
     if (nbits != 4) return E4Q_ERR_BAD_NBITS;
     if (index_bytes != 4 && index_bytes != 8) return E4Q_ERR_BAD_DTYPE;
-    if (rows < 0 || dim <= 0 || dim > E4Q_MAX_DIM || n_indices < 0 || n_bags < 0) return E4Q_ERR_BAD_SHAPE;
+    if (rows < 0 || rows > E4Q_MAX_ROWS || dim <= 0 || dim > E4Q_MAX_DIM || n_indices < 0 || n_bags < 0 ||
+        n_bags > E4Q_MAX_ROWS)
+        return E4Q_ERR_BAD_SHAPE;
     if (n_bags == 0) return E4Q_OK;
     if (!offsets || !out || (n_indices > 0 && !indices)) return E4Q_ERR_NULL_POINTER;
     if (rows > 0 && (!codes || !scale_f16 || !bias_f16)) return E4Q_ERR_NULL_POINTER;
@@ -280,7 +281,8 @@ int e4q_fuse_rows(const uint8_t* codes, const uint16_t* scale_f16, const uint16_
                   int32_t dim, int32_t nbits, int64_t row_pitch, uint8_t* fused, void* hip_stream)
 {
     if (nbits != 4) return E4Q_ERR_BAD_NBITS;
-    if (rows < 0 || dim <= 0 || dim > E4Q_MAX_DIM || (row_pitch & 1) || row_pitch < fused_min_pitch(dim))
+    if (rows < 0 || rows > E4Q_MAX_ROWS || dim <= 0 || dim > E4Q_MAX_DIM || (row_pitch & 1) ||
+        row_pitch < fused_min_pitch(dim) || row_pitch > 0x7ffffffeLL)
         return E4Q_ERR_BAD_SHAPE;
     if (rows == 0) return E4Q_OK;
     if (!codes || !scale_f16 || !bias_f16 || !fused) return E4Q_ERR_NULL_POINTER;
@@ -296,7 +298,8 @@ int e4q_sparse_lengths_sum_fused(const uint8_t* fused, int64_t rows, int32_t dim
 {
     if (nbits != 4) return E4Q_ERR_BAD_NBITS;
     if (index_bytes != 4 && index_bytes != 8) return E4Q_ERR_BAD_DTYPE;
-    if (rows < 0 || dim <= 0 || dim > E4Q_MAX_DIM || n_indices < 0 || n_bags < 0 || (row_pitch & 1) ||
+    if (rows < 0 || rows > E4Q_MAX_ROWS || dim <= 0 || dim > E4Q_MAX_DIM || n_indices < 0 || n_bags < 0 ||
+        n_bags > E4Q_MAX_ROWS || (row_pitch & 1) ||
         row_pitch < fused_min_pitch(dim))
         return E4Q_ERR_BAD_SHAPE;
     if (n_bags == 0) return E4Q_OK;
@@ -314,7 +317,7 @@ const char* e4q_strerror(int code)
     switch (code) {
         case E4Q_OK: return "success";
         case E4Q_ERR_NULL_POINTER: return "a required pointer is NULL";
-        case E4Q_ERR_BAD_SHAPE: return "bad shape: need rows >= 0, 0 < dim <= 4096, row_stride >= dim, an even row_pitch >= e4q_fused_row_bytes(dim)";
+        case E4Q_ERR_BAD_SHAPE: return "bad shape: need 0 <= rows <= 2^31, 0 < dim <= 4096, row_stride >= dim, an even row_pitch >= e4q_fused_row_bytes(dim)";
         case E4Q_ERR_BAD_NBITS: return "nbits must be 2, 4 or 8 for the uniform quantizer and its dequantizer, 4 for the lookup operator";
         case E4Q_ERR_BAD_SEARCH: return "bad search parameters: need n_bins >= 1, 0 <= ratio < 1, lloyd_iters >= 0";
         case E4Q_ERR_BAD_DTYPE: return "dtype must be E4Q_F32 (0) or E4Q_F16 (1); index_bytes must be 4 or 8";

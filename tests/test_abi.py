@@ -87,6 +87,7 @@ def test_validation_rejects_bad_arguments_before_any_launch(lib):
     assert call(ratio=-0.1) == -4
     assert call(dtype=2) == -5
     assert call(rows=-1) == -2
+    assert call(rows=2 ** 31 + 1) == -2
     assert call(dim=0) == -2
     assert call(dim=4097) == -2
     assert call(stride=63) == -2

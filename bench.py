@@ -33,10 +33,12 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# MI355X: 256 CUs x 4 SIMDs x 16 fp32 lanes at 2.4 GHz, one plain (non-packed) VALU operation per
-# lane per clock.  The data-sheet 157.3 TFLOP/s is this figure x 2 (packed fp32) x 2 (FMA = 2 flops);
-# packed fp32 is switched off in this build and 7 of the 8 operations per element are not FMAs.
-PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
+# MI355X: 256 CUs x 4 SIMDs at 2.4 GHz; a SIMD retires a wave64 binary32 add, multiply or multiply-add
+# in 2 clocks (32 lanes per clock, measured with plain, non-packed instructions), which is the
+# data-sheet 157.3 TFLOP/s at 2 flops per multiply-add.  One lane-op = one such operation on one lane.
+# Rounding, clamping, compares, selects, conversions and binary64 operations retire at half that rate,
+# so a kernel whose mix contains them cannot reach 1.0 of this peak.
+PEAK_LANE_OPS = 256 * 4 * 32 * 2.4e9
 PEAK_HBM_BYTES = 8.0e12
 
 WORKLOADS = {
@@ -237,7 +239,7 @@ def bench_batch(args, e4q, synth, torch, params) -> int:
                    "step": "quantize_rowwise_greedy_batch over all tables (grouped launches per dimension)"},
         "kernels": {"greedy_rpl_group_kernel (all launches of a step)": {"avg_ms": ms, "rows_per_s": rows / (ms * 1e-3)}},
         "roofline": {"kernel": "greedy_rpl_group_kernel", "bound": "alu", "achieved": ops / (ms * 1e-3) / 1e12,
-                     "peak": PEAK_LANE_OPS / 1e12, "unit": "T lane-op/s (plain fp32 VALU: 256 CU x 64 lanes x 2.4 GHz)",
+                     "peak": PEAK_LANE_OPS / 1e12, "unit": "T lane-op/s (fp32 VALU: 256 CU x 128 lanes x 2.4 GHz = 157.3 TFLOP/s / 2)",
                      "frac": ops / (ms * 1e-3) / PEAK_LANE_OPS, "hbm_achieved_GBps": nbytes / (ms * 1e-3) / 1e9,
                      "traffic": None},
     }
@@ -388,7 +390,7 @@ def main() -> int:
         },
         "roofline": {
             "kernel": q_name, "bound": "alu", "achieved": achieved / 1e12,
-            "peak": PEAK_LANE_OPS / 1e12, "unit": "T lane-op/s (plain fp32 VALU: 256 CU x 64 lanes x 2.4 GHz)",
+            "peak": PEAK_LANE_OPS / 1e12, "unit": "T lane-op/s (fp32 VALU: 256 CU x 128 lanes x 2.4 GHz = 157.3 TFLOP/s / 2)",
             "frac": achieved / PEAK_LANE_OPS,
             "lane_ops_per_row": ops_per_row,
             "bytes_per_row": q_bytes // rows,

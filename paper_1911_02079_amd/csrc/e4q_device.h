@@ -21,7 +21,16 @@ namespace e4q {
 constexpr float kQMax4 = 15.0f;  // 2^n - 1 for n = 4 (Eq. 1); the codebook grid uses it directly
 
 // Value after a round trip through binary16 (RNE; v_cvt_f16_f32 then v_cvt_f32_f16).
-__device__ __forceinline__ float through_f16(float v) { return (float)(_Float16)v; }
+// Hides where a binary32 value came from.  Without it the compiler folds the widening of a binary16
+// value into every multiply-add that uses it (the mixed-precision form of the instruction), which
+// issues at a fraction of the plain binary32 rate; the result is the same either way.
+__device__ __forceinline__ float opaque(float v)
+{
+    asm("" : "+v"(v));
+    return v;
+}
+
+__device__ __forceinline__ float through_f16(float v) { return opaque((float)(_Float16)v); }
 
 __device__ __forceinline__ uint16_t f16_bits(float v)
 {
@@ -31,7 +40,7 @@ __device__ __forceinline__ uint16_t f16_bits(float v)
 
 __device__ __forceinline__ float f16_bits_to_float(uint16_t b)
 {
-    return (float)__builtin_bit_cast(_Float16, b);
+    return opaque((float)__builtin_bit_cast(_Float16, b));
 }
 
 // The parameters that are stored for the clipping range [lo, hi] (Eq. 1 with binary16 storage):

@@ -4,10 +4,10 @@
 // One table row per lane, the row in registers (dimension a compile-time constant), the 16 centres
 // in registers.  Per Lloyd round each element scans the 16 centres for the first nearest one
 // (binary32 distances, strict '<', so equal distances keep the lower index) and adds its value to
-// that cluster's binary64 sum; the sums and counts live in a lane-private column of LDS because
-// the cluster index is only known at run time (a register array cannot be indexed by it).  LDS
-// operations of a wave execute in order, so a cluster's sum is accumulated in element order, which
-// is what makes the result reproducible bit for bit.  Means are one binary64 division per
+// that cluster's binary64 sum; the sums and counts live in a lane-private column of LDS (16 KB per
+// wave) because the cluster index is only known at run time (a register array cannot be indexed by
+// it).  LDS operations of a wave execute in order, so a cluster's sum is accumulated in element
+// order, which is what makes the result reproducible bit for bit.  Means are one binary64 division per
 // non-empty cluster and round; empty clusters keep their centre.  After the fixed number of rounds
 // the centres are rounded to binary16 and every element is assigned once more against the rounded
 // codebook, so the stored indices and the stored codebook agree.
@@ -49,33 +49,42 @@ __device__ __forceinline__ void grid_centres(float lo, float hi, float (&c)[kK])
     for (int k = 0; k < kK; ++k) c[k] = __builtin_fmaf((float)k, step, lo);
 }
 
-// Lane-private accumulators: entry k of lane l sits at [k * 64 + l].
+// Lane-private accumulators: the record of cluster k and lane l sits at [k * 64 + l]; sum and
+// count share a record so one address serves both.
+struct LloydRec {
+    double sum;
+    uint32_t cnt;
+    uint32_t pad;
+};
 struct LloydScratch {
-    double sum[kK * 64];
-    uint32_t cnt[kK * 64];
+    LloydRec rec[kK * 64];
 };
 
 __device__ __forceinline__ void lloyd_clear(LloydScratch& s, int lane)
 {
 #pragma unroll
     for (int k = 0; k < kK; ++k) {
-        s.sum[k * 64 + lane] = 0.0;
-        s.cnt[k * 64 + lane] = 0u;
+        s.rec[k * 64 + lane].sum = 0.0;
+        s.rec[k * 64 + lane].cnt = 0u;
     }
 }
 
+// The adds are LDS read-modify-write instructions without a return value (one instruction each
+// instead of read, add, write): no other lane touches the record, and a wave's LDS instructions
+// execute in program order, so the sum still grows in element order.
 __device__ __forceinline__ void lloyd_add(LloydScratch& s, int lane, int a, float x)
 {
-    s.sum[a * 64 + lane] += (double)x;
-    s.cnt[a * 64 + lane] += 1u;
+    LloydRec* r = &s.rec[a * 64 + lane];
+    __hip_atomic_fetch_add(&r->sum, (double)x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+    __hip_atomic_fetch_add(&r->cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
 }
 
 __device__ __forceinline__ void lloyd_update(const LloydScratch& s, int lane, float (&c)[kK])
 {
 #pragma unroll
     for (int k = 0; k < kK; ++k) {
-        const uint32_t n = s.cnt[k * 64 + lane];
-        const float mean = (float)(s.sum[k * 64 + lane] / (double)n);
+        const uint32_t n = s.rec[k * 64 + lane].cnt;
+        const float mean = (float)(s.rec[k * 64 + lane].sum / (double)n);
         c[k] = n > 0u ? mean : c[k];
     }
 }

@@ -114,6 +114,67 @@ __device__ __forceinline__ float tree_sum(Leaf&& leaf)
     }
 }
 
+// Eq. 2 restricted to elements LO .. LO+SPAN-1 (those below D) of a row held in registers, summed
+// over the same adjacent-pair tree as tree_sum.  MASKED drops elements at or beyond `nvalid`.
+//
+// Below kStage elements the arithmetic runs one step at a time over the whole block with the
+// instruction order pinned, instead of element by element: the compiler's own order keeps two
+// elements in flight, too few to cover the result latency with three waves on a SIMD.  On gfx950 a
+// wave64 binary32 add, multiply or multiply-add occupies the SIMD for 2 clocks, while rounding and
+// the three-operand clamp take 4; the wave lowers its priority for the run of those two steps and
+// raises it again afterwards, so that waves in their cheap steps are issued first and the others
+// fill in (measured 4 % to 12 % over no hint; priorities inside a kernel only order waves of a SIMD).
+constexpr int kStage = 4;
+
+template <int LO, int SPAN, int D, bool MASKED>
+__device__ __forceinline__ float tree_sq_err(const float (&x)[D], const StoredParams& p, int nvalid)
+{
+    static_assert(LO < D, "empty subtree");
+    if constexpr (SPAN <= kStage) {
+        constexpr int N = (D - LO) < SPAN ? (D - LO) : SPAN;
+        float t[N];
+#pragma unroll
+        for (int i = 0; i < N; ++i) t[i] = x[LO + i] - p.bias;
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < N; ++i) t[i] = t[i] * p.inv;
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_setprio(0);
+#pragma unroll
+        for (int i = 0; i < N; ++i) t[i] = __builtin_rintf(t[i]);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < N; ++i) t[i] = __builtin_amdgcn_fmed3f(t[i], 0.0f, p.qmax);
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+        for (int i = 0; i < N; ++i) t[i] = __builtin_fmaf(t[i], p.scale, p.bias);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < N; ++i) t[i] = x[LO + i] - t[i];
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int i = 0; i < N; ++i) t[i] = t[i] * t[i];
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (MASKED) {
+#pragma unroll
+            for (int i = 0; i < N; ++i) t[i] = (LO + i < nvalid) ? t[i] : 0.0f;
+        }
+        const float s = tree_sum<0, SPAN, N>([&](auto k) { return t[decltype(k)::value]; });
+        __builtin_amdgcn_sched_barrier(0);
+        return s;
+    } else {
+        constexpr int H = SPAN / 2;
+        if constexpr (LO + H >= D) {
+            return tree_sq_err<LO, H, D, MASKED>(x, p, nvalid);  // right half is padding
+        } else {
+            const float a = tree_sq_err<LO, H, D, MASKED>(x, p, nvalid);
+            const float b = tree_sq_err<LO + H, H, D, MASKED>(x, p, nvalid);
+            return a + b;
+        }
+    }
+}
+
 // Packs N codes of NBITS bits (8/NBITS per byte, first element in the lowest bits) into 32-bit words.
 // `code(Idx<k>)` returns element k's code as an unsigned integer (0 for elements that do not exist).
 template <int NBITS, class Code, int... K>

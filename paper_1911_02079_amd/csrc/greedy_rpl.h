@@ -67,7 +67,7 @@ template <int D>
 __device__ __forceinline__ float range_loss(const float (&x)[D], float lo, float hi, float qmax)
 {
     const StoredParams p = stored_params(lo, hi, qmax);
-    return tree_sum<0, next_pow2(D), D>([&](auto k) { return elem_sq_err(x[decltype(k)::value], p); });
+    return tree_sq_err<0, next_pow2(D), D, false>(x, p, D);
 }
 
 // The whole path for the row this lane owns: load, min/max, Algorithm 1, encode, store.

@@ -71,16 +71,11 @@ __device__ __forceinline__ float swl_range_loss(const float (&x)[E], int nvalid,
         const int nblocks = nvalid / 8;
         part = tree_sum<0, E / 8, E / 8>([&](auto b) {
             constexpr int blk = decltype(b)::value;
-            const float bs = tree_sum<8 * blk, 8, E>([&](auto k) { return elem_sq_err(x[decltype(k)::value], p); });
+            const float bs = tree_sq_err<8 * blk, 8, E, false>(x, p, E);
             return (blk < nblocks) ? bs : 0.0f;
         });
     } else {
-        part = tree_sum<0, E, E>([&](auto k) {
-            constexpr int e = decltype(k)::value;
-            const float s = elem_sq_err(x[e], p);
-            if constexpr (MASK == 2) return (e < nvalid) ? s : 0.0f;
-            else return s;
-        });
+        part = tree_sq_err<0, E, E, MASK == 2>(x, p, nvalid);
     }
     return group_reduce<L>(part, [](float a, float b) { return a + b; });
 }

@@ -162,9 +162,11 @@ def test_few_rows_every_layout(e4q, oracle_lib, dim, dtype):
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.float16])
-@pytest.mark.parametrize("dim", [4, 12, 20, 36, 50, 100, 127, 136, 192, 200, 256, 300, 512, 1000, 1024, 2048])
+@pytest.mark.parametrize("dim", [4, 12, 20, 36, 50, 100, 127, 136, 192, 200, 256, 300, 512, 1000, 1001, 1024, 2047,
+                                 2048, 2500])
 def test_many_rows_long_chunks(e4q, oracle_lib, dim, dtype):
-    """Many rows and a dimension without a one-row-per-lane kernel: up to 128 elements per lane."""
+    """Many rows and a dimension without a one-row-per-lane kernel: up to 128 elements per lane, 32 (64 beyond
+    dim 2048) when the dimension is not a multiple of 8."""
     from helpers import oracle_rows_in_parallel
     from paper_1911_02079_amd import synth
 

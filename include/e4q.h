@@ -137,6 +137,11 @@ int e4q_quantize_rowwise_greedy_batch(const e4q_table_desc* descs, int32_t n_tab
  *   idx            [out] rows x ceil(dim/2) bytes, two indices per byte, low nibble first
  *   centroids_f16  [out] rows x 16 binary16 values (32 bytes per row, dense)
  * Bytes per row: dim/2 + 32 (the KMEANS (FP16) sizes of Table 3).
+ *
+ * Diagnostic switch: with E4Q_KMEANS_FORCE_SCAN=1 in the environment (read at every call) the
+ * kernels find the nearest centre by scanning all 16 instead of bisecting the ordered centres; the
+ * outputs are the same bit for bit, only slower.  It exists so that the scan, which otherwise runs
+ * only for rows whose centres fall out of order, can be exercised.
  */
 int e4q_quantize_rowwise_kmeans16(const void* table, int dtype, int64_t rows, int32_t dim,
                                   int64_t row_stride, int32_t lloyd_iters, uint8_t* idx,

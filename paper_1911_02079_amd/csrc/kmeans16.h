@@ -12,9 +12,11 @@
 // the centres are rounded to binary16 and every element is assigned once more against the rounded
 // codebook, so the stored indices and the stored codebook agree.
 //
-// Arithmetic per element and round: 16 subtractions, 8 three-input minimums, 15 compares, 15 selects
-// and one binary64 add: about 55 VALU operations; the path is bound by VALU issue like the greedy
-// search.  Rows with dim <= 16 need no clustering (every value is its own codebook entry).
+// Arithmetic per element and round, as the scan defines it: 16 subtractions, 8 three-input minimums,
+// 15 compares, 15 selects and one binary64 add: about 55 operations; the path is bound by VALU issue
+// like the greedy search.  With the centres in order (checked every round) the index comes from a
+// bisection instead, 4 compares and 11 selects.  Rows with dim <= 16 need no clustering (every value
+// is its own codebook entry).
 #pragma once
 
 #include "greedy_rpl.h"  // load_row
@@ -42,6 +44,47 @@ __device__ __forceinline__ int nearest_centre(float x, const float (&c)[kK])
     return idx;
 }
 
+// The same index when the centres are in non-decreasing order.  Then s[k] = x - c[k] (rounded) is
+// non-increasing in k, "s[k] > m" (m the smallest distance) holds exactly for the centres before the
+// first nearest one, and a four-step bisection over that predicate finds their number: 4 compares and
+// 11 selects instead of 15 and 15.  The probe positions 7; 3|11; 1|5|9|13; 0|2|..|14 are picked by
+// selects on the earlier outcomes, because a register array cannot be indexed at run time.
+__device__ __forceinline__ int nearest_centre_sorted(float x, const float (&c)[kK])
+{
+    float s[kK];
+#pragma unroll
+    for (int k = 0; k < kK; ++k) s[k] = x - c[k];
+    float m = __builtin_fminf(__builtin_fminf(__builtin_fabsf(s[0]), __builtin_fabsf(s[1])), __builtin_fabsf(s[2]));
+#pragma unroll
+    for (int k = 3; k + 1 < kK; k += 2)
+        m = __builtin_fminf(__builtin_fminf(m, __builtin_fabsf(s[k])), __builtin_fabsf(s[k + 1]));
+    m = __builtin_fminf(m, __builtin_fabsf(s[kK - 1]));
+    const bool b3 = s[7] > m;
+    const float p2 = b3 ? s[11] : s[3];
+    const bool b2 = p2 > m;
+    const float u0 = b3 ? s[9] : s[1], u1 = b3 ? s[13] : s[5];
+    const float p1 = b2 ? u1 : u0;
+    const bool b1 = p1 > m;
+    const float v0 = b3 ? s[8] : s[0], v1 = b3 ? s[10] : s[2], v2 = b3 ? s[12] : s[4], v3 = b3 ? s[14] : s[6];
+    const float w0 = b2 ? v2 : v0, w1 = b2 ? v3 : v1;
+    const float p0 = b1 ? w1 : w0;
+    const bool b0 = p0 > m;
+    return (b3 ? 8 : 0) | (b2 ? 4 : 0) | (b1 ? 2 : 0) | (b0 ? 1 : 0);
+}
+
+// True when every lane of the wave holds centres in non-decreasing order.  A grid is, and a Lloyd
+// round keeps them so as long as every point goes to a centre of its own Voronoi cell; a point that
+// ties between two centres through rounding goes to the lower index and can pull that centre past
+// the other one.  No input is known to do that, but the order is checked every round rather than
+// assumed, and a wave that fails the check scans all 16 centres (same results, more work).
+__device__ __forceinline__ bool wave_centres_sorted(const float (&c)[kK])
+{
+    bool ok = true;
+#pragma unroll
+    for (int k = 0; k + 1 < kK; ++k) ok = ok && (c[k] <= c[k + 1]);
+    return __builtin_amdgcn_ballot_w64(!ok) == 0;
+}
+
 __device__ __forceinline__ void grid_centres(float lo, float hi, float (&c)[kK])
 {
     const float step = (hi - lo) / kQMax4;
@@ -49,42 +92,41 @@ __device__ __forceinline__ void grid_centres(float lo, float hi, float (&c)[kK])
     for (int k = 0; k < kK; ++k) c[k] = __builtin_fmaf((float)k, step, lo);
 }
 
-// Lane-private accumulators: the record of cluster k and lane l sits at [k * 64 + l]; sum and
-// count share a record so one address serves both.
-struct LloydRec {
-    double sum;
-    uint32_t cnt;
-    uint32_t pad;
-};
+// Lane-private accumulators: slot k * 64 + l belongs to cluster k of lane l.  Sums and counts both
+// sit in 8-byte slots, the counts 8 KB after the sums, so that one address serves both (the second
+// access is the same register plus a constant offset) and a wave's 64 slots of one access are
+// consecutive in LDS: the binary64 accesses then hit every bank evenly.  (Sum and count side by side
+// in one 16-byte record was measured with bank conflicts in 47 % of the LDS cycles.)
 struct LloydScratch {
-    LloydRec rec[kK * 64];
+    double sum[kK * 64];
+    uint2 cnt[kK * 64];
 };
 
 __device__ __forceinline__ void lloyd_clear(LloydScratch& s, int lane)
 {
 #pragma unroll
     for (int k = 0; k < kK; ++k) {
-        s.rec[k * 64 + lane].sum = 0.0;
-        s.rec[k * 64 + lane].cnt = 0u;
+        s.sum[k * 64 + lane] = 0.0;
+        s.cnt[k * 64 + lane].x = 0u;
     }
 }
 
 // The adds are LDS read-modify-write instructions without a return value (one instruction each
-// instead of read, add, write): no other lane touches the record, and a wave's LDS instructions
+// instead of read, add, write): no other lane touches the slot, and a wave's LDS instructions
 // execute in program order, so the sum still grows in element order.
 __device__ __forceinline__ void lloyd_add(LloydScratch& s, int lane, int a, float x)
 {
-    LloydRec* r = &s.rec[a * 64 + lane];
-    __hip_atomic_fetch_add(&r->sum, (double)x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
-    __hip_atomic_fetch_add(&r->cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+    const int slot = a * 64 + lane;
+    __hip_atomic_fetch_add(&s.sum[slot], (double)x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+    __hip_atomic_fetch_add(&s.cnt[slot].x, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
 }
 
 __device__ __forceinline__ void lloyd_update(const LloydScratch& s, int lane, float (&c)[kK])
 {
 #pragma unroll
     for (int k = 0; k < kK; ++k) {
-        const uint32_t n = s.rec[k * 64 + lane].cnt;
-        const float mean = (float)(s.rec[k * 64 + lane].sum / (double)n);
+        const uint32_t n = s.cnt[k * 64 + lane].x;
+        const float mean = (float)(s.sum[k * 64 + lane] / (double)n);
         c[k] = n > 0u ? mean : c[k];
     }
 }
@@ -127,10 +169,20 @@ __global__ void __launch_bounds__(64) kmeans16_rpl_kernel(KMeansArgs a)
     float c[kK];
     grid_centres(lo, hi, c);
 
+    const Tin* src = static_cast<const Tin*>(a.table) + r * a.row_stride;
     for (int it = 0; it < a.lloyd_iters; ++it) {
         lloyd_clear(scratch, lane);
+        if (!a.force_scan && wave_centres_sorted(c)) {
 #pragma unroll
-        for (int e = 0; e < D; ++e) lloyd_add(scratch, lane, nearest_centre(x[e], c), x[e]);
+            for (int e = 0; e < D; ++e) lloyd_add(scratch, lane, nearest_centre_sorted(x[e], c), x[e]);
+        } else {
+            // rolled, re-reading the row: x[] cannot be indexed by a loop counter
+#pragma unroll 1
+            for (int e = 0; e < D; ++e) {
+                const float v = (float)src[e];
+                lloyd_add(scratch, lane, nearest_centre(v, c), v);
+            }
+        }
         lloyd_update(scratch, lane, c);
     }
 
@@ -139,12 +191,25 @@ __global__ void __launch_bounds__(64) kmeans16_rpl_kernel(KMeansArgs a)
     uint32_t w[NWORDS];
 #pragma unroll
     for (int k = 0; k < kK; ++k) ch[k] = through_f16(c[k]);
+    if (a.force_scan || !wave_centres_sorted(ch)) {
+        if (live) {
+            store_codebook(c, a.centroids_f16 + row * kK);
+            uint8_t* out = a.idx + row * (D / 2);
+#pragma unroll 1
+            for (int b = 0; b < D / 2; ++b) {
+                const uint32_t q0 = (uint32_t)nearest_centre((float)src[2 * b], ch);
+                const uint32_t q1 = (uint32_t)nearest_centre((float)src[2 * b + 1], ch);
+                out[b] = (uint8_t)(q0 | (q1 << 4));
+            }
+        }
+        return;
+    }
 #pragma unroll
     for (int i = 0; i < NWORDS; ++i) {
         uint32_t acc = 0;
 #pragma unroll
         for (int e = 0; e < 8; ++e)
-            if (8 * i + e < D) acc |= (uint32_t)nearest_centre(x[8 * i + e], ch) << (4 * e);
+            if (8 * i + e < D) acc |= (uint32_t)nearest_centre_sorted(x[8 * i + e], ch) << (4 * e);
         w[i] = acc;
     }
     if (!live) return;

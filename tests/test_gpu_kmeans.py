@@ -114,6 +114,44 @@ def test_edge_cases(e4q, oracle_lib):
         e4q.quantize_rowwise_kmeans16(big, -1)
 
 
+def clumped_rows(rows, dim, seed):
+    """Rows made of a few tight clumps (widths of 0..8 units in the last place) at positions spread
+    over seven decades, some clumps nearly on top of each other: centres that coincide, stay empty,
+    or differ by one unit in the last place, which is where the order of the centres is at stake."""
+    rng = np.random.default_rng(seed)
+    out = np.empty((rows, dim), np.float32)
+    for r in range(rows):
+        k = int(rng.integers(2, 7))
+        pos = (10.0 ** rng.uniform(-3, 4, size=k)) * rng.choice([-1.0, 1.0], size=k)
+        if rng.random() < 0.5:
+            pos[1] = np.float32(pos[0]) * (1.0 + rng.uniform(0, 4e-7))
+        width = rng.choice([0, 1, 2, 8], size=k)
+        which = rng.integers(0, k, size=dim)
+        vals = pos[which].astype(np.float32)
+        steps = rng.integers(0, 1 + width[which])
+        for _ in range(8):
+            m = steps > 0
+            vals[m] = np.nextafter(vals[m], np.float32(np.inf))
+            steps = steps - 1
+        out[r] = vals
+    return out
+
+
+@pytest.mark.parametrize("dim", [24, 64, 128])
+def test_clumped_rows_and_forced_scan(e4q, oracle_lib, dim, monkeypatch):
+    """The bisection over ordered centres and the 16-centre scan give the oracle's result on rows with
+    coinciding and nearly coinciding centres; the scan is forced through the diagnostic switch."""
+    t = torch.from_numpy(clumped_rows(4_099, dim, 900 + dim)).cuda()
+    idx, cent = compare(e4q, oracle_lib, t, 6, "clumped rows, bisection")
+    monkeypatch.setenv("E4Q_KMEANS_FORCE_SCAN", "1")
+    idx2, cent2 = compare(e4q, oracle_lib, t, 6, "clumped rows, forced scan")
+    assert torch.equal(idx, idx2) and torch.equal(cent.view(torch.int16), cent2.view(torch.int16))
+    from paper_1911_02079_amd import synth
+
+    g = synth.mixture_table(5_003, dim, device="cuda")
+    compare(e4q, oracle_lib, g, 20, "mixture rows, forced scan")
+
+
 def test_full_config5_mixture_2M_x_64(e4q, oracle_lib):
     """Every row of the benchmark configuration, in the launch configuration bench.py times."""
     from paper_1911_02079_amd import synth

@@ -121,13 +121,23 @@ __device__ __forceinline__ void lloyd_add(LloydScratch& s, int lane, int a, floa
     __hip_atomic_fetch_add(&s.cnt[slot].x, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
 }
 
+// All 32 LDS reads are issued before the first division and the 16 divisions carry no branch, so
+// their dependent chains (about 15 binary64 instructions each) interleave instead of running one
+// after the other behind an LDS round trip each.
 __device__ __forceinline__ void lloyd_update(const LloydScratch& s, int lane, float (&c)[kK])
 {
+    uint32_t n[kK];
+    double sum[kK];
 #pragma unroll
     for (int k = 0; k < kK; ++k) {
-        const uint32_t n = s.cnt[k * 64 + lane].x;
-        const float mean = (float)(s.sum[k * 64 + lane] / (double)n);
-        c[k] = n > 0u ? mean : c[k];
+        n[k] = s.cnt[k * 64 + lane].x;
+        sum[k] = s.sum[k * 64 + lane];
+    }
+#pragma unroll
+    for (int k = 0; k < kK; ++k) {
+        float mean = (float)(sum[k] / (double)(n[k] > 0u ? n[k] : 1u));
+        asm volatile("" : "+v"(mean));  // keeps the division out of a per-cluster branch
+        c[k] = n[k] > 0u ? mean : c[k];
     }
 }
 

@@ -44,6 +44,26 @@ int validate_table(const void* table, int dtype, int64_t rows, int32_t dim, int6
     return E4Q_OK;
 }
 
+// Estimated duration of the greedy search, in SIMD cycles, for `rows` rows with `elems` elements per
+// lane and `lanes` lanes per row.  Instructions per wave and scored range: 8 per element, about 48 of
+// per-range scalar work (two divisions, two binary16 round trips, the decisions) and 6 per butterfly
+// step.  Cycles per instruction as measured on gfx950: a SIMD with one or two waves issues one
+// instruction per wave every 5.2 cycles (so two waves cost what one costs), three waves 8.3 in total,
+// four or more 2.45 each.  Fitted on 20 k - 1 M rows at dim 32 / 64 / 128; within 10 % of the
+// measured times except where the next smaller layout is equally fast.
+double layout_cost(int64_t rows, int32_t elems, int32_t lanes, int32_t n_iter, bool row_per_lane)
+{
+    int steps = 0;
+    while ((1 << steps) < lanes) ++steps;
+    const double per_range = 8.0 * elems + 48.0 + 6.0 * steps;
+    const double instructions = (1.0 + 2.0 * n_iter) * per_range + 10.0 * elems;
+    const int64_t rows_per_block = row_per_lane ? 64 : 256 / lanes;
+    const int64_t waves = (rows + rows_per_block - 1) / rows_per_block * (row_per_lane ? 1 : 4);
+    const int64_t per_simd = (waves + 1023) / 1024;
+    const double cycles_per_instruction = per_simd <= 2 ? 5.2 : per_simd == 3 ? 8.3 : 2.45 * (double)per_simd;
+    return instructions * cycles_per_instruction;
+}
+
 int enqueue_greedy(const void* table, int dtype, int64_t rows, int32_t dim, int64_t row_stride, int32_t nbits,
                    int32_t n_bins, int32_t n_iter, uint8_t* codes, uint16_t* scale_f16,
                    uint16_t* bias_f16, hipStream_t stream)
@@ -64,34 +84,46 @@ int enqueue_greedy(const void* table, int dtype, int64_t rows, int32_t dim, int6
     a.nbits = nbits;
     a.qmax = (float)((1 << nbits) - 1);
 
-    // Kernel choice.  One row per lane (rows/64 waves, rows in registers, ~3 % overhead over the
-    // algorithmic operation count) is the cheapest way to do the arithmetic and is used whenever the
-    // table has enough rows to occupy the chip and the dimension has an instantiation.  Otherwise a
-    // row is spread over L lanes with E contiguous elements each: E = 8 when parallelism or
-    // coalescing matters most (few rows; ratio == 0, which is bound by HBM), E up to 128 when the
-    // table is large but its dimension has no one-row-per-lane kernel -- at most 32 if the dimension
-    // is not a multiple of 8, where every element carries its own validity mask and 32 of them are
-    // what the scalar registers hold without spilling (measured: dim 100 takes 2.7 ms per 2 M rows
-    // with E = 32, 6.0 ms with E = 128).
-    const int64_t rpl_waves = (rows + 63) / 64;
-    const bool few_rows = rpl_waves < 512;  // under half a wave per SIMD
+    // Kernel choice.  One row per lane (rows/64 waves, the row in registers, ~3 % overhead over the
+    // algorithmic operation count) does the arithmetic with the fewest instructions; a row spread over
+    // L lanes with E contiguous elements each (E * L >= dim) repeats the per-range scalar work in every
+    // lane but makes L times as many waves.  Which is faster depends on how many waves a SIMD gets:
+    // see layout_cost.  ratio == 0 is bound by HBM and always takes E = 8 (a wave then reads and
+    // writes contiguous memory).
+    int E = 0, L = 1;  // E == 0: one row per lane
+    if (n_iter == 0) {
+        E = dim <= 512 ? 8 : dim <= 1024 ? 16 : dim <= 2048 ? 32 : 64;
+    } else {
+        double best = e4q::rpl_supports_dim(dim) ? layout_cost(rows, dim, 1, n_iter, true) : -1.0;
+        // A dimension that is not a multiple of 8 carries one validity mask per element; 32 of them
+        // are what the scalar registers hold without spilling (measured: dim 100 takes 2.7 ms per
+        // 2 M rows with E = 32, 6.0 ms with E = 128).
+        const int e_max = dim % 8 == 0 ? 128 : (dim <= 2048 ? 32 : 64);
+        for (int e = 8; e <= e_max; e *= 2) {
+            if (e > 8 && e / 2 >= dim) break;  // more than half of every lane would be padding
+            int l = 1;
+            while (e * l < dim) l *= 2;
+            if (l > (e == 128 ? 32 : 64)) continue;
+            const double c = layout_cost(rows, e, l, n_iter, false);
+            if (best < 0.0 || c < best) {
+                best = c;
+                E = e;
+                L = l;
+            }
+        }
+    }
     hipError_t err;
-    if (e4q::rpl_supports_dim(dim) && n_iter > 0 && !few_rows) {
+    if (E == 0) {
         err = dtype == E4Q_F32 ? e4q::launch_greedy_rpl_f32(a, dim, stream)
                                : e4q::launch_greedy_rpl_f16(a, dim, stream);
     } else {
-        int E;
-        if (n_iter == 0 || few_rows)
-            E = dim <= 512 ? 8 : dim <= 1024 ? 16 : dim <= 2048 ? 32 : 64;
-        else if (dim % 8 != 0)
-            E = dim <= 8 ? 8 : dim <= 16 ? 16 : dim <= 2048 ? 32 : 64;
-        else
-            E = dim <= 8 ? 8 : dim <= 16 ? 16 : dim <= 32 ? 32 : dim <= 64 ? 64 : 128;
-        int L = 1;
         while (E * L < dim) L *= 2;
         if (E == 128)
             err = dtype == E4Q_F32 ? e4q::launch_greedy_swl_f32_big(a, dim, E, L, stream)
                                    : e4q::launch_greedy_swl_f16_big(a, dim, E, L, stream);
+        else if (E >= 32)
+            err = dtype == E4Q_F32 ? e4q::launch_greedy_swl_f32_mid(a, dim, E, L, stream)
+                                   : e4q::launch_greedy_swl_f16_mid(a, dim, E, L, stream);
         else
             err = dtype == E4Q_F32 ? e4q::launch_greedy_swl_f32_small(a, dim, E, L, stream)
                                    : e4q::launch_greedy_swl_f16_small(a, dim, E, L, stream);

@@ -53,10 +53,13 @@ hipError_t launch_greedy_rpl_f16(const GreedyArgs& a, int32_t dim, hipStream_t s
 hipError_t launch_greedy_rpl_group_f32(const GreedyGroup& g, int32_t dim, hipStream_t stream);
 hipError_t launch_greedy_rpl_group_f16(const GreedyGroup& g, int32_t dim, hipStream_t stream);
 // Sub-wave layouts: L lanes per row, E contiguous elements per lane (see greedy_swl.h).
-// "small": E in {8, 16, 32, 64}; "big": E = 128.  Needs dim <= E * L.
+// "small": E in {8, 16}; "mid": E in {32, 64}; "big": E = 128.  L is a power of two up to 64 (32 for E = 128);
+// needs dim <= E * L.
 hipError_t launch_greedy_swl_f32_small(const GreedyArgs& a, int32_t dim, int E, int L, hipStream_t stream);
+hipError_t launch_greedy_swl_f32_mid(const GreedyArgs& a, int32_t dim, int E, int L, hipStream_t stream);
 hipError_t launch_greedy_swl_f32_big(const GreedyArgs& a, int32_t dim, int E, int L, hipStream_t stream);
 hipError_t launch_greedy_swl_f16_small(const GreedyArgs& a, int32_t dim, int E, int L, hipStream_t stream);
+hipError_t launch_greedy_swl_f16_mid(const GreedyArgs& a, int32_t dim, int E, int L, hipStream_t stream);
 hipError_t launch_greedy_swl_f16_big(const GreedyArgs& a, int32_t dim, int E, int L, hipStream_t stream);
 
 // Arguments of the codebook (16-means) kernels.

@@ -1,8 +1,7 @@
-// Sub-wave greedy kernels, short chunks per lane (8 to 64 elements), _Float16 tables.
-#define E4Q_SWL_LAYOUTS                                                                          \
+// Sub-wave greedy kernels, 8 or 16 elements per lane, _Float16 tables.
+#define E4Q_SWL_LAYOUTS \
     E4Q_SWL(8, 1) E4Q_SWL(8, 2) E4Q_SWL(8, 4) E4Q_SWL(8, 8) E4Q_SWL(8, 16) E4Q_SWL(8, 32) E4Q_SWL(8, 64) \
-    E4Q_SWL(16, 1) E4Q_SWL(16, 64) E4Q_SWL(32, 1) E4Q_SWL(32, 2) E4Q_SWL(32, 4) E4Q_SWL(32, 8)            \
-    E4Q_SWL(32, 16) E4Q_SWL(32, 32) E4Q_SWL(32, 64) E4Q_SWL(64, 1) E4Q_SWL(64, 64)
+    E4Q_SWL(16, 1) E4Q_SWL(16, 2) E4Q_SWL(16, 4) E4Q_SWL(16, 8) E4Q_SWL(16, 16) E4Q_SWL(16, 32) E4Q_SWL(16, 64)
 #include "greedy_swl.h"
 
 namespace e4q {

@@ -180,6 +180,26 @@ def test_many_rows_long_chunks(e4q, oracle_lib, dim, dtype):
     assert bad.size == 0, f"{bad.size} rows differ, first {bad[:5]}"
 
 
+@pytest.mark.parametrize("rows,dim,dtype", [(33_000, 32, torch.float32), (33_000, 64, torch.float32),
+                                            (33_000, 128, torch.float32), (50_000, 64, torch.float16),
+                                            (65_536, 128, torch.float32), (150_000, 32, torch.float16),
+                                            (150_000, 64, torch.float32), (150_000, 128, torch.float32),
+                                            (200_000, 128, torch.float16), (100_000, 96, torch.float32)])
+def test_mid_sized_tables(e4q, oracle_lib, rows, dim, dtype):
+    """Tables of one to six waves per SIMD, where the host spreads a row over 2 to 8 lanes (16 to 64
+    elements per lane) instead of keeping it in one: every row against the oracle."""
+    from helpers import oracle_rows_in_parallel
+    from paper_1911_02079_amd import synth
+
+    t = synth.gaussian_table(rows, dim, 0.1, seed=5000 + rows % 977 + dim, device="cuda").to(dtype)
+    say(f"mid-sized table rows={rows} dim={dim} {dtype}")
+    codes, scale, bias = e4q.quantize_rowwise_greedy(t, 40, 0.2)
+    torch.cuda.synchronize()
+    o = oracle_rows_in_parallel(oracle_lib, t.cpu().numpy(), 40, 0.2)
+    bad = np.flatnonzero((codes.cpu().numpy() != o[0]).any(axis=1) | (f16_bits(scale) != o[1]) | (f16_bits(bias) != o[2]))
+    assert bad.size == 0, f"{bad.size} rows differ, first {bad[:5]}"
+
+
 def test_largest_dimension(e4q, oracle_lib):
     from paper_1911_02079_amd import synth
 

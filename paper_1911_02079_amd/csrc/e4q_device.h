@@ -79,15 +79,6 @@ __device__ __forceinline__ float quantize_elem(float x, const StoredParams& p)
     return __builtin_amdgcn_fmed3f(__builtin_rintf(t), 0.0f, p.qmax);
 }
 
-// Squared reconstruction error of one element (one term of Eq. 2): 8 VALU operations.
-__device__ __forceinline__ float elem_sq_err(float x, const StoredParams& p)
-{
-    float q = quantize_elem(x, p);
-    float xh = __builtin_fmaf(q, p.scale, p.bias);
-    float e = x - xh;
-    return e * e;
-}
-
 // Balanced adjacent-pair sum of leaf(LO) .. leaf(min(LO+SPAN, D)-1); SPAN is a power of two.
 // `leaf` is called with a compile-time index (std::integral_constant style) so that rows held in
 // registers stay in registers.
@@ -116,6 +107,7 @@ __device__ __forceinline__ float tree_sum(Leaf&& leaf)
 
 // Eq. 2 restricted to elements LO .. LO+SPAN-1 (those below D) of a row held in registers, summed
 // over the same adjacent-pair tree as tree_sum.  MASKED drops elements at or beyond `nvalid`.
+// Per element: quantize_elem's three steps, then xh = fma(q, scale, bias), e = x - xh, e * e.
 //
 // Below kStage elements the arithmetic runs one step at a time over the whole block with the
 // instruction order pinned, instead of element by element: the compiler's own order keeps two

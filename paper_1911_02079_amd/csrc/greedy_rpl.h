@@ -9,7 +9,7 @@
 //
 // Memory access: lane l reads row (base + l) in 16-byte pieces; across the wave these are 64
 // different cache lines per instruction, which costs a few thousand cycles per wave once, against
-// some 270 000 cycles of arithmetic for D = 128 -- the kernel is bound by VALU issue, not by HBM.
+// some 150 000 cycles of arithmetic for D = 128 -- the kernel is bound by VALU issue, not by HBM.
 // Codes go out as 16-byte (or 4-byte) stores per lane into the dense code array, scale and bias
 // as one 2-byte store per lane (128 contiguous bytes per wave).
 #pragma once

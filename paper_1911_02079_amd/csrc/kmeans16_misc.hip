@@ -36,9 +36,16 @@ __global__ void __launch_bounds__(64) kmeans16_any_kernel(KMeansArgs a, int32_t 
     grid_centres(lo, hi, c);
     for (int it = 0; it < a.lloyd_iters; ++it) {
         lloyd_clear(scratch, lane);
-        for (int e = 0; e < d; ++e) {
-            const float v = (float)src[e];
-            lloyd_add(scratch, lane, nearest_centre(v, c), v);
+        if (!a.force_scan && wave_centres_sorted(c)) {  // uniform over the wave's live lanes
+            for (int e = 0; e < d; ++e) {
+                const float v = (float)src[e];
+                lloyd_add(scratch, lane, nearest_centre_sorted(v, c), v);
+            }
+        } else {
+            for (int e = 0; e < d; ++e) {
+                const float v = (float)src[e];
+                lloyd_add(scratch, lane, nearest_centre(v, c), v);
+            }
         }
         lloyd_update(scratch, lane, c);
     }
@@ -48,10 +55,18 @@ __global__ void __launch_bounds__(64) kmeans16_any_kernel(KMeansArgs a, int32_t 
         cb[k] = f16_bits(c[k]);
         ch[k] = through_f16(c[k]);
     }
-    for (int b = 0; b < nbytes; ++b) {
-        const uint32_t q0 = (uint32_t)nearest_centre((float)src[2 * b], ch);
-        const uint32_t q1 = (2 * b + 1 < d) ? (uint32_t)nearest_centre((float)src[2 * b + 1], ch) : 0u;
-        out[b] = (uint8_t)(q0 | (q1 << 4));
+    if (!a.force_scan && wave_centres_sorted(ch)) {
+        for (int b = 0; b < nbytes; ++b) {
+            const uint32_t q0 = (uint32_t)nearest_centre_sorted((float)src[2 * b], ch);
+            const uint32_t q1 = (2 * b + 1 < d) ? (uint32_t)nearest_centre_sorted((float)src[2 * b + 1], ch) : 0u;
+            out[b] = (uint8_t)(q0 | (q1 << 4));
+        }
+    } else {
+        for (int b = 0; b < nbytes; ++b) {
+            const uint32_t q0 = (uint32_t)nearest_centre((float)src[2 * b], ch);
+            const uint32_t q1 = (2 * b + 1 < d) ? (uint32_t)nearest_centre((float)src[2 * b + 1], ch) : 0u;
+            out[b] = (uint8_t)(q0 | (q1 << 4));
+        }
     }
 }
 

@@ -94,7 +94,8 @@ int enqueue_greedy(const void* table, int dtype, int64_t rows, int32_t dim, int6
     if (n_iter == 0) {
         E = dim <= 512 ? 8 : dim <= 1024 ? 16 : dim <= 2048 ? 32 : 64;
     } else {
-        double best = e4q::rpl_supports_dim(dim) ? layout_cost(rows, dim, 1, n_iter, true) : -1.0;
+        const bool rpl = e4q::rpl_supports_dim(dim) || e4q::rpl_tail_supports_dim(dim);
+        double best = rpl ? layout_cost(rows, (dim + 7) / 8 * 8, 1, n_iter, true) : -1.0;
         // A dimension that is not a multiple of 8 carries one validity mask per element; 32 of them
         // are what the scalar registers hold without spilling (measured: dim 100 takes 2.7 ms per
         // 2 M rows with E = 32, 6.0 ms with E = 128).
@@ -113,9 +114,12 @@ int enqueue_greedy(const void* table, int dtype, int64_t rows, int32_t dim, int6
         }
     }
     hipError_t err;
-    if (E == 0) {
+    if (E == 0 && dim % 8 == 0) {
         err = dtype == E4Q_F32 ? e4q::launch_greedy_rpl_f32(a, dim, stream)
                                : e4q::launch_greedy_rpl_f16(a, dim, stream);
+    } else if (E == 0) {
+        err = dtype == E4Q_F32 ? e4q::launch_greedy_rpl_tail_f32(a, dim, stream)
+                               : e4q::launch_greedy_rpl_tail_f16(a, dim, stream);
     } else {
         while (E * L < dim) L *= 2;
         if (E == 128)

@@ -106,7 +106,8 @@ __device__ __forceinline__ float tree_sum(Leaf&& leaf)
 }
 
 // Eq. 2 restricted to elements LO .. LO+SPAN-1 (those below D) of a row held in registers, summed
-// over the same adjacent-pair tree as tree_sum.  MASKED drops elements at or beyond `nvalid`.
+// over the same adjacent-pair tree as tree_sum.  MASKED drops elements at or beyond `nvalid`;
+// elements below VALID_BELOW are known to exist and carry no test.
 // Per element: quantize_elem's three steps, then xh = fma(q, scale, bias), e = x - xh, e * e.
 //
 // Below kStage elements the arithmetic runs one step at a time over the whole block with the
@@ -118,7 +119,7 @@ __device__ __forceinline__ float tree_sum(Leaf&& leaf)
 // fill in (measured 4 % to 12 % over no hint; priorities inside a kernel only order waves of a SIMD).
 constexpr int kStage = 4;
 
-template <int LO, int SPAN, int D, bool MASKED>
+template <int LO, int SPAN, int D, bool MASKED, int VALID_BELOW = 0>
 __device__ __forceinline__ float tree_sq_err(const float (&x)[D], const StoredParams& p, int nvalid)
 {
     static_assert(LO < D, "empty subtree");
@@ -150,7 +151,8 @@ __device__ __forceinline__ float tree_sq_err(const float (&x)[D], const StoredPa
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (MASKED) {
 #pragma unroll
-            for (int i = 0; i < N; ++i) t[i] = (LO + i < nvalid) ? t[i] : 0.0f;
+            for (int i = 0; i < N; ++i)
+                if (LO + i >= VALID_BELOW) t[i] = (LO + i < nvalid) ? t[i] : 0.0f;
         }
         const float s = tree_sum<0, SPAN, N>([&](auto k) { return t[decltype(k)::value]; });
         __builtin_amdgcn_sched_barrier(0);
@@ -158,10 +160,10 @@ __device__ __forceinline__ float tree_sq_err(const float (&x)[D], const StoredPa
     } else {
         constexpr int H = SPAN / 2;
         if constexpr (LO + H >= D) {
-            return tree_sq_err<LO, H, D, MASKED>(x, p, nvalid);  // right half is padding
+            return tree_sq_err<LO, H, D, MASKED, VALID_BELOW>(x, p, nvalid);  // right half is padding
         } else {
-            const float a = tree_sq_err<LO, H, D, MASKED>(x, p, nvalid);
-            const float b = tree_sq_err<LO + H, H, D, MASKED>(x, p, nvalid);
+            const float a = tree_sq_err<LO, H, D, MASKED, VALID_BELOW>(x, p, nvalid);
+            const float b = tree_sq_err<LO + H, H, D, MASKED, VALID_BELOW>(x, p, nvalid);
             return a + b;
         }
     }

@@ -46,10 +46,14 @@ struct GreedyGroup {
 
 // Register-resident kernels exist for these dimensions (multiples of 8 up to 128).
 inline bool rpl_supports_dim(int32_t dim) { return dim >= 8 && dim <= 128 && dim % 8 == 0; }
+// Row per lane with a masked tail: any other dimension below 128 (registers for the next multiple of 8).
+inline bool rpl_tail_supports_dim(int32_t dim) { return dim >= 1 && dim < 128 && dim % 8 != 0; }
 
 // Each returns hipGetLastError() after enqueueing.
 hipError_t launch_greedy_rpl_f32(const GreedyArgs& a, int32_t dim, hipStream_t stream);
 hipError_t launch_greedy_rpl_f16(const GreedyArgs& a, int32_t dim, hipStream_t stream);
+hipError_t launch_greedy_rpl_tail_f32(const GreedyArgs& a, int32_t dim, hipStream_t stream);
+hipError_t launch_greedy_rpl_tail_f16(const GreedyArgs& a, int32_t dim, hipStream_t stream);
 hipError_t launch_greedy_rpl_group_f32(const GreedyGroup& g, int32_t dim, hipStream_t stream);
 hipError_t launch_greedy_rpl_group_f16(const GreedyGroup& g, int32_t dim, hipStream_t stream);
 // Sub-wave layouts: L lanes per row, E contiguous elements per lane (see greedy_swl.h).

@@ -62,23 +62,41 @@ __device__ __forceinline__ void load_row(const _Float16* __restrict__ row, bool 
     for (int k = 0; k < D; ++k) x[k] = (float)row[k];
 }
 
-// Eq. 2 for the range [lo, hi] on a row held in registers.
-template <int D>
-__device__ __forceinline__ float range_loss(const float (&x)[D], float lo, float hi, float qmax)
+// Eq. 2 for the range [lo, hi] on a row held in registers.  With TAIL the row has d elements,
+// D - 8 < d < D: the last few registers hold no element and their terms are dropped.  (Padding the
+// tree with zeros up to a larger power of two changes no sum, so D's tree serves d.)
+template <int D, bool TAIL>
+__device__ __forceinline__ float range_loss(const float (&x)[D], float lo, float hi, float qmax, int d)
 {
     const StoredParams p = stored_params(lo, hi, qmax);
-    return tree_sq_err<0, next_pow2(D), D, false>(x, p, D);
+    return tree_sq_err<0, next_pow2(D), D, TAIL, D - 7>(x, p, d);
 }
 
 // The whole path for the row this lane owns: load, min/max, Algorithm 1, encode, store.
-template <int D, typename Tin>
-__device__ __forceinline__ void greedy_rpl_row(const GreedyArgs& a, int64_t row)
+// TAIL: the dimension d is not a multiple of 8 (D - 8 < d < D); registers at and beyond d copy element 0,
+// which leaves min and max alone, and are masked out of the loss and the codes.  d is the same for
+// every lane, so the masks are scalar conditions.
+template <int D, typename Tin, bool TAIL = false>
+__device__ __forceinline__ void greedy_rpl_row(const GreedyArgs& a, int64_t row, int d = D)
 {
     const bool live = row < a.rows;
     const int64_t r = live ? row : a.rows - 1;  // tail lanes redo the last row and store nothing
 
     float x[D];
-    load_row<D>(static_cast<const Tin*>(a.table) + r * a.row_stride, a.vec_loads != 0, x);
+    if constexpr (TAIL) {
+        // the first D - 8 elements always exist and load like a row of that dimension
+        const Tin* src = static_cast<const Tin*>(a.table) + r * a.row_stride;
+        if constexpr (D > 8) {
+            float head[D - 8];
+            load_row<D - 8>(src, a.vec_loads != 0, head);
+#pragma unroll
+            for (int k = 0; k < D - 8; ++k) x[k] = head[k];
+        }
+#pragma unroll
+        for (int k = D - 8; k < D; ++k) x[k] = (float)src[k < d ? k : 0];
+    } else {
+        load_row<D>(static_cast<const Tin*>(a.table) + r * a.row_stride, a.vec_loads != 0, x);
+    }
 
     // Algorithm 1, lines 1-2: the starting range is the row's range.
     float lo0 = x[0], hi0 = x[0];
@@ -92,12 +110,12 @@ __device__ __forceinline__ void greedy_rpl_row(const GreedyArgs& a, int64_t row)
     if (a.n_iter > 0) {  // uniform branch: ratio == 0 needs no scoring at all
         const float stepsize = (hi0 - lo0) / a.n_bins;
         float cur_lo = lo0, cur_hi = hi0;
-        float best = range_loss<D>(x, lo0, hi0, a.qmax);
+        float best = range_loss<D, TAIL>(x, lo0, hi0, a.qmax, d);
         for (int it = 0; it < a.n_iter; ++it) {
             const float next_lo = cur_lo + stepsize;
             const float next_hi = cur_hi - stepsize;
-            const float loss_l = range_loss<D>(x, next_lo, cur_hi, a.qmax);
-            const float loss_r = range_loss<D>(x, cur_lo, next_hi, a.qmax);
+            const float loss_l = range_loss<D, TAIL>(x, next_lo, cur_hi, a.qmax, d);
+            const float loss_r = range_loss<D, TAIL>(x, cur_lo, next_hi, a.qmax, d);
             const bool left = loss_l < loss_r;  // a tie moves the upper bound
             cur_lo = left ? next_lo : cur_lo;
             cur_hi = left ? cur_hi : next_hi;
@@ -120,9 +138,9 @@ __device__ __forceinline__ void greedy_rpl_row(const GreedyArgs& a, int64_t row)
     }
     auto encode = [&](auto nb) {
         constexpr int NB = decltype(nb)::value;
-        constexpr int NBYTES = D * NB / 8;
-        const uint32_t cls = (NBYTES % 16 == 0 && a.vec_stores == 2) ? 2u : ((NBYTES % 4 == 0 && a.vec_stores >= 1) ? 1u : 0u);
-        encode_chunks<NB, D, 0, false>(x, p, D, a.codes + row * NBYTES, cls, live);
+        const int nbytes = TAIL ? (d * NB + 7) / 8 : D * NB / 8;  // bytes per row; rows are dense
+        const uint32_t cls = (nbytes % 16 == 0 && a.vec_stores == 2) ? 2u : ((nbytes % 4 == 0 && a.vec_stores >= 1) ? 1u : 0u);
+        encode_chunks<NB, D, 0, TAIL>(x, p, d, a.codes + row * nbytes, cls, live);
     };
     if (a.nbits == 4) encode(Idx<4>{});  // uniform branches
     else if (a.nbits == 8) encode(Idx<8>{});
@@ -133,6 +151,13 @@ template <int D, typename Tin>
 __global__ void __launch_bounds__(kRplBlock) greedy_rpl_kernel(GreedyArgs a)
 {
     greedy_rpl_row<D, Tin>(a, (int64_t)blockIdx.x * kRplBlock + threadIdx.x);
+}
+
+// The same for a dimension d that is not a multiple of 8, D = d rounded up.
+template <int D, typename Tin>
+__global__ void __launch_bounds__(kRplBlock) greedy_rpl_tail_kernel(GreedyArgs a, int32_t d)
+{
+    greedy_rpl_row<D, Tin, true>(a, (int64_t)blockIdx.x * kRplBlock + threadIdx.x, d);
 }
 
 // Several tables of one dimension and input type in one launch: workgroup b belongs to the first
@@ -175,6 +200,16 @@ inline hipError_t launch_greedy_rpl(const GreedyArgs& a, hipStream_t stream)
 {
     const int64_t blocks = (a.rows + kRplBlock - 1) / kRplBlock;
     hipLaunchKernelGGL((greedy_rpl_kernel<D, Tin>), dim3((unsigned)blocks), dim3(kRplBlock), 0, stream, a);
+    return hipGetLastError();
+}
+
+// Needs D - 8 < d < D.
+template <int D, typename Tin>
+inline hipError_t launch_greedy_rpl_tail(const GreedyArgs& a, int32_t d, hipStream_t stream)
+{
+    if (d <= D - 8 || d >= D) return hipErrorInvalidValue;
+    const int64_t blocks = (a.rows + kRplBlock - 1) / kRplBlock;
+    hipLaunchKernelGGL((greedy_rpl_tail_kernel<D, Tin>), dim3((unsigned)blocks), dim3(kRplBlock), 0, stream, a, d);
     return hipGetLastError();
 }
 

@@ -63,4 +63,34 @@ inline hipError_t dispatch_greedy_rpl_group(const GreedyGroup& g, int32_t dim, h
     }
 }
 
+// Dimensions below 128 that are not multiples of 8: the kernel for the next multiple of 8.
+template <typename Tin>
+inline hipError_t dispatch_greedy_rpl_tail(const GreedyArgs& a, int32_t dim, hipStream_t stream)
+{
+    switch ((dim + 7) / 8 * 8) {
+#define E4Q_CASE(D) \
+    case D:         \
+        return launch_greedy_rpl_tail<D, Tin>(a, dim, stream);
+        E4Q_CASE(8)
+        E4Q_CASE(16)
+        E4Q_CASE(24)
+        E4Q_CASE(32)
+        E4Q_CASE(40)
+        E4Q_CASE(48)
+        E4Q_CASE(56)
+        E4Q_CASE(64)
+        E4Q_CASE(72)
+        E4Q_CASE(80)
+        E4Q_CASE(88)
+        E4Q_CASE(96)
+        E4Q_CASE(104)
+        E4Q_CASE(112)
+        E4Q_CASE(120)
+        E4Q_CASE(128)
+#undef E4Q_CASE
+        default:
+            return hipErrorInvalidValue;
+    }
+}
+
 }  // namespace e4q

@@ -162,11 +162,11 @@ def test_few_rows_every_layout(e4q, oracle_lib, dim, dtype):
 
 
 @pytest.mark.parametrize("dtype", [torch.float32, torch.float16])
-@pytest.mark.parametrize("dim", [4, 12, 20, 36, 50, 100, 127, 136, 192, 200, 256, 300, 512, 1000, 1001, 1024, 2047,
-                                 2048, 2500])
+@pytest.mark.parametrize("dim", [1, 2, 3, 4, 7, 9, 12, 15, 17, 20, 31, 33, 36, 50, 63, 65, 100, 121, 127, 129, 136, 192,
+                                 200, 256, 300, 512, 1000, 1001, 1024, 2047, 2048, 2500])
 def test_many_rows_long_chunks(e4q, oracle_lib, dim, dtype):
-    """Many rows and a dimension without a one-row-per-lane kernel: up to 128 elements per lane, 32 (64 beyond
-    dim 2048) when the dimension is not a multiple of 8."""
+    """Many rows and a dimension that is not a multiple of 8 (below 128: one row per lane with a masked tail;
+    above: 32 or 64 elements per lane) or above 128 (up to 128 elements per lane)."""
     from helpers import oracle_rows_in_parallel
     from paper_1911_02079_amd import synth
 
@@ -184,7 +184,9 @@ def test_many_rows_long_chunks(e4q, oracle_lib, dim, dtype):
                                             (33_000, 128, torch.float32), (50_000, 64, torch.float16),
                                             (65_536, 128, torch.float32), (150_000, 32, torch.float16),
                                             (150_000, 64, torch.float32), (150_000, 128, torch.float32),
-                                            (200_000, 128, torch.float16), (100_000, 96, torch.float32)])
+                                            (200_000, 128, torch.float16), (100_000, 96, torch.float32),
+                                            (40_000, 100, torch.float32), (120_000, 50, torch.float16),
+                                            (70_000, 127, torch.float32)])
 def test_mid_sized_tables(e4q, oracle_lib, rows, dim, dtype):
     """Tables of one to six waves per SIMD, where the host spreads a row over 2 to 8 lanes (16 to 64
     elements per lane) instead of keeping it in one: every row against the oracle."""

@@ -77,7 +77,7 @@ __device__ __forceinline__ float range_loss(const float (&x)[D], float lo, float
 // which leaves min and max alone, and are masked out of the loss and the codes.  d is the same for
 // every lane, so the masks are scalar conditions.
 template <int D, typename Tin, bool TAIL = false>
-__device__ __forceinline__ void greedy_rpl_row(const GreedyArgs& a, int64_t row, int d = D)
+__device__ __forceinline__ void greedy_rpl_row(const GreedyArgs& a, int64_t row, int d = D, uint8_t* stage = nullptr)
 {
     const bool live = row < a.rows;
     const int64_t r = live ? row : a.rows - 1;  // tail lanes redo the last row and store nothing
@@ -139,8 +139,13 @@ __device__ __forceinline__ void greedy_rpl_row(const GreedyArgs& a, int64_t row,
     auto encode = [&](auto nb) {
         constexpr int NB = decltype(nb)::value;
         const int nbytes = TAIL ? (d * NB + 7) / 8 : D * NB / 8;  // bytes per row; rows are dense
-        const uint32_t cls = (nbytes % 16 == 0 && a.vec_stores == 2) ? 2u : ((nbytes % 4 == 0 && a.vec_stores >= 1) ? 1u : 0u);
-        encode_chunks<NB, D, 0, TAIL>(x, p, d, a.codes + row * nbytes, cls, live);
+        if constexpr (TAIL) {
+            // into the wave's staging area, which mirrors its 64 dense rows; the kernel copies it out
+            encode_chunks<NB, D, 0, true>(x, p, d, stage + (int)threadIdx.x * nbytes, 0u, true);
+        } else {
+            const uint32_t cls = (nbytes % 16 == 0 && a.vec_stores == 2) ? 2u : ((nbytes % 4 == 0 && a.vec_stores >= 1) ? 1u : 0u);
+            encode_chunks<NB, D, 0, false>(x, p, d, a.codes + row * nbytes, cls, live);
+        }
     };
     if (a.nbits == 4) encode(Idx<4>{});  // uniform branches
     else if (a.nbits == 8) encode(Idx<8>{});
@@ -154,10 +159,32 @@ __global__ void __launch_bounds__(kRplBlock) greedy_rpl_kernel(GreedyArgs a)
 }
 
 // The same for a dimension d that is not a multiple of 8, D = d rounded up.
+// Rows of d * nbits / 8 bytes are not multiples of 4 bytes long, so a lane cannot store its row in
+// words; the wave's 64 rows are contiguous in memory, though, and start at a multiple of 64 bytes.
+// Each lane packs its row into LDS (8 KiB, an image of those 64 rows) and the wave copies the image out
+// 16 bytes per lane at a time.
 template <int D, typename Tin>
 __global__ void __launch_bounds__(kRplBlock) greedy_rpl_tail_kernel(GreedyArgs a, int32_t d)
 {
-    greedy_rpl_row<D, Tin, true>(a, (int64_t)blockIdx.x * kRplBlock + threadIdx.x, d);
+    __shared__ __attribute__((aligned(16))) uint8_t stage[kRplBlock * D];  // D bytes per row cover 8-bit codes
+    const int64_t row0 = (int64_t)blockIdx.x * kRplBlock;
+    greedy_rpl_row<D, Tin, true>(a, row0 + threadIdx.x, d, stage);
+    __syncthreads();
+    const int nbytes = (d * a.nbits + 7) / 8;
+    const int64_t rows_here = a.rows - row0 < kRplBlock ? a.rows - row0 : kRplBlock;
+    const int total = (int)rows_here * nbytes;
+    uint8_t* dst = a.codes + row0 * nbytes;
+    if (a.vec_stores == 2) {  // 16-byte aligned buffer: 64 * nbytes keeps every wave's start aligned
+        for (int off = (int)threadIdx.x * 16; off < total; off += kRplBlock * 16) {
+            if (off + 16 <= total) {
+                *reinterpret_cast<uint4*>(dst + off) = *reinterpret_cast<const uint4*>(stage + off);
+            } else {
+                for (int b = off; b < total; ++b) dst[b] = stage[b];
+            }
+        }
+    } else {
+        for (int b = (int)threadIdx.x; b < total; b += kRplBlock) dst[b] = stage[b];
+    }
 }
 
 // Several tables of one dimension and input type in one launch: workgroup b belongs to the first

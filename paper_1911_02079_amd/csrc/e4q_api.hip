@@ -272,7 +272,7 @@ int e4q_quantize_rowwise_kmeans16(const void* table, int dtype, int64_t rows, in
     a.idx = idx;
     a.centroids_f16 = centroids_f16;
     a.vec_loads = (aligned(table, 16) && (row_stride * esz) % 16 == 0) ? 1u : 0u;
-    a.vec_stores = aligned(idx, 4) ? 1u : 0u;
+    a.vec_stores = aligned(idx, 16) ? 2u : (aligned(idx, 4) ? 1u : 0u);
     const char* scan = std::getenv("E4Q_KMEANS_FORCE_SCAN");
     a.force_scan = (scan && scan[0] == '1') ? 1u : 0u;
     const hipError_t err = e4q::launch_kmeans16(a, dtype, dim, static_cast<hipStream_t>(hip_stream));

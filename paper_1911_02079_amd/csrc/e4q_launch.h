@@ -75,7 +75,7 @@ struct KMeansArgs {
     uint8_t* idx;
     uint16_t* centroids_f16;
     uint32_t vec_loads;   // 1: table base and row pitch are 16-byte aligned
-    uint32_t vec_stores;  // >= 1: idx base is 4-byte aligned
+    uint32_t vec_stores;  // >= 1: idx base is 4-byte aligned; 2: 16-byte aligned
     uint32_t force_scan;  // 1: always scan all 16 centres (diagnostic; results are identical)
 };
 hipError_t launch_kmeans16(const KMeansArgs& a, int dtype, int32_t dim, hipStream_t stream);

@@ -158,18 +158,33 @@ __device__ __forceinline__ void store_codebook(const float (&c)[kK], uint16_t* _
     }
 }
 
-template <int D, typename Tin>
-__global__ void __launch_bounds__(64) kmeans16_rpl_kernel(KMeansArgs a)
+// TAIL: the dimension d is not a multiple of 8 (D - 8 < d < D, the same for every lane).  Registers at
+// and beyond d copy element 0 (min and max are unaffected), are skipped by scalar branches in the
+// rounds and pack as index 0; a row of (d + 1) / 2 bytes is not a whole number of words, so the wave's
+// 64 dense rows are assembled in LDS (in the accumulators' space, free by then) and copied out 16 bytes
+// per lane at a time.
+template <int D, typename Tin, bool TAIL>
+__device__ __forceinline__ void kmeans16_rpl_body(const KMeansArgs& a, int d, LloydScratch& scratch)
 {
     static_assert(D > kK, "rows with dim <= 16 take the other kernel");
-    __shared__ LloydScratch scratch;
     const int lane = threadIdx.x;
-    const int64_t row = (int64_t)blockIdx.x * 64 + lane;
+    const int64_t row0 = (int64_t)blockIdx.x * 64;
+    const int64_t row = row0 + lane;
     const bool live = row < a.rows;
     const int64_t r = live ? row : a.rows - 1;
+    const Tin* src = static_cast<const Tin*>(a.table) + r * a.row_stride;
 
     float x[D];
-    load_row<D>(static_cast<const Tin*>(a.table) + r * a.row_stride, a.vec_loads != 0, x);
+    if constexpr (TAIL) {
+        float head[D - 8];
+        load_row<D - 8>(src, a.vec_loads != 0, head);
+#pragma unroll
+        for (int k = 0; k < D - 8; ++k) x[k] = head[k];
+#pragma unroll
+        for (int k = D - 8; k < D; ++k) x[k] = (float)src[k < d ? k : 0];
+    } else {
+        load_row<D>(src, a.vec_loads != 0, x);
+    }
     float lo = x[0], hi = x[0];
 #pragma unroll
     for (int k = 1; k < D; ++k) {
@@ -179,16 +194,16 @@ __global__ void __launch_bounds__(64) kmeans16_rpl_kernel(KMeansArgs a)
     float c[kK];
     grid_centres(lo, hi, c);
 
-    const Tin* src = static_cast<const Tin*>(a.table) + r * a.row_stride;
     for (int it = 0; it < a.lloyd_iters; ++it) {
         lloyd_clear(scratch, lane);
         if (!a.force_scan && wave_centres_sorted(c)) {
 #pragma unroll
-            for (int e = 0; e < D; ++e) lloyd_add(scratch, lane, nearest_centre_sorted(x[e], c), x[e]);
+            for (int e = 0; e < D; ++e)
+                if (!TAIL || e < D - 7 || e < d) lloyd_add(scratch, lane, nearest_centre_sorted(x[e], c), x[e]);
         } else {
             // rolled, re-reading the row: x[] cannot be indexed by a loop counter
 #pragma unroll 1
-            for (int e = 0; e < D; ++e) {
+            for (int e = 0; e < d; ++e) {
                 const float v = (float)src[e];
                 lloyd_add(scratch, lane, nearest_centre(v, c), v);
             }
@@ -198,17 +213,18 @@ __global__ void __launch_bounds__(64) kmeans16_rpl_kernel(KMeansArgs a)
 
     float ch[kK];
     constexpr int NWORDS = (D / 2 + 3) / 4;
+    const int nbytes = (d + 1) / 2;
     uint32_t w[NWORDS];
 #pragma unroll
     for (int k = 0; k < kK; ++k) ch[k] = through_f16(c[k]);
     if (a.force_scan || !wave_centres_sorted(ch)) {
         if (live) {
             store_codebook(c, a.centroids_f16 + row * kK);
-            uint8_t* out = a.idx + row * (D / 2);
+            uint8_t* out = a.idx + row * nbytes;
 #pragma unroll 1
-            for (int b = 0; b < D / 2; ++b) {
+            for (int b = 0; b < nbytes; ++b) {
                 const uint32_t q0 = (uint32_t)nearest_centre((float)src[2 * b], ch);
-                const uint32_t q1 = (uint32_t)nearest_centre((float)src[2 * b + 1], ch);
+                const uint32_t q1 = (2 * b + 1 < d) ? (uint32_t)nearest_centre((float)src[2 * b + 1], ch) : 0u;
                 out[b] = (uint8_t)(q0 | (q1 << 4));
             }
         }
@@ -219,20 +235,60 @@ __global__ void __launch_bounds__(64) kmeans16_rpl_kernel(KMeansArgs a)
         uint32_t acc = 0;
 #pragma unroll
         for (int e = 0; e < 8; ++e)
-            if (8 * i + e < D) acc |= (uint32_t)nearest_centre_sorted(x[8 * i + e], ch) << (4 * e);
+            if (8 * i + e < D) {
+                const uint32_t q = (uint32_t)nearest_centre_sorted(x[8 * i + e], ch);
+                acc |= ((!TAIL || 8 * i + e < D - 7 || 8 * i + e < d) ? q : 0u) << (4 * e);
+            }
         w[i] = acc;
     }
-    if (!live) return;
-    store_codebook(c, a.centroids_f16 + row * kK);
-    uint8_t* out = a.idx + row * (D / 2);
-    if (a.vec_stores >= 1) {
-        uint32_t* o = reinterpret_cast<uint32_t*>(out);
+    if (live) store_codebook(c, a.centroids_f16 + row * kK);
+    if constexpr (TAIL) {
+        uint8_t* stage = reinterpret_cast<uint8_t*>(scratch.sum);  // 8 KiB; 64 rows of at most 64 bytes
+        __syncthreads();
 #pragma unroll
-        for (int i = 0; i < NWORDS; ++i) o[i] = w[i];
+        for (int b = 0; b < D / 2; ++b)
+            if (b < nbytes) stage[lane * nbytes + b] = (uint8_t)(w[b / 4] >> (8 * (b % 4)));
+        __syncthreads();
+        const int64_t rows_here = a.rows - row0 < 64 ? a.rows - row0 : 64;
+        const int total = (int)rows_here * nbytes;
+        uint8_t* dst = a.idx + row0 * nbytes;
+        if (a.vec_stores == 2) {  // 16-byte aligned buffer: 64 * nbytes keeps every wave's start aligned
+            for (int off = lane * 16; off < total; off += 64 * 16) {
+                if (off + 16 <= total) {
+                    *reinterpret_cast<uint4*>(dst + off) = *reinterpret_cast<const uint4*>(stage + off);
+                } else {
+                    for (int b = off; b < total; ++b) dst[b] = stage[b];
+                }
+            }
+        } else {
+            for (int b = lane; b < total; b += 64) dst[b] = stage[b];
+        }
     } else {
+        if (!live) return;
+        uint8_t* out = a.idx + row * (D / 2);
+        if (a.vec_stores >= 1) {
+            uint32_t* o = reinterpret_cast<uint32_t*>(out);
 #pragma unroll
-        for (int b = 0; b < D / 2; ++b) out[b] = (uint8_t)(w[b / 4] >> (8 * (b % 4)));
+            for (int i = 0; i < NWORDS; ++i) o[i] = w[i];
+        } else {
+#pragma unroll
+            for (int b = 0; b < D / 2; ++b) out[b] = (uint8_t)(w[b / 4] >> (8 * (b % 4)));
+        }
     }
+}
+
+template <int D, typename Tin>
+__global__ void __launch_bounds__(64) kmeans16_rpl_kernel(KMeansArgs a)
+{
+    __shared__ LloydScratch scratch;
+    kmeans16_rpl_body<D, Tin, false>(a, D, scratch);
+}
+
+template <int D, typename Tin>
+__global__ void __launch_bounds__(64) kmeans16_rpl_tail_kernel(KMeansArgs a, int32_t d)
+{
+    __shared__ LloydScratch scratch;
+    kmeans16_rpl_body<D, Tin, true>(a, d, scratch);
 }
 
 // Launches the register-resident kernel for `dim` if there is one; returns false otherwise.
@@ -244,6 +300,25 @@ inline bool launch_kmeans16_rpl(const KMeansArgs& a, int32_t dim, hipStream_t st
 #define E4Q_CASE(D) \
     case D:         \
         hipLaunchKernelGGL((kmeans16_rpl_kernel<D, Tin>), grid, block, 0, stream, a); \
+        return true;
+        E4Q_CASE(24) E4Q_CASE(32) E4Q_CASE(40) E4Q_CASE(48) E4Q_CASE(56) E4Q_CASE(64) E4Q_CASE(72)
+        E4Q_CASE(80) E4Q_CASE(88) E4Q_CASE(96) E4Q_CASE(104) E4Q_CASE(112) E4Q_CASE(120) E4Q_CASE(128)
+#undef E4Q_CASE
+        default:
+            return false;
+    }
+}
+
+// The same for 16 < dim < 128, dim % 8 != 0: the kernel of the next multiple of 8 with a masked tail.
+template <typename Tin>
+inline bool launch_kmeans16_rpl_tail(const KMeansArgs& a, int32_t dim, hipStream_t stream)
+{
+    if (dim <= kK || dim >= 128 || dim % 8 == 0) return false;
+    const dim3 grid((unsigned)((a.rows + 63) / 64)), block(64);
+    switch ((dim + 7) / 8 * 8) {
+#define E4Q_CASE(D) \
+    case D:         \
+        hipLaunchKernelGGL((kmeans16_rpl_tail_kernel<D, Tin>), grid, block, 0, stream, a, dim); \
         return true;
         E4Q_CASE(24) E4Q_CASE(32) E4Q_CASE(40) E4Q_CASE(48) E4Q_CASE(56) E4Q_CASE(64) E4Q_CASE(72)
         E4Q_CASE(80) E4Q_CASE(88) E4Q_CASE(96) E4Q_CASE(104) E4Q_CASE(112) E4Q_CASE(120) E4Q_CASE(128)

@@ -6,6 +6,8 @@ namespace e4q {
 
 bool launch_kmeans16_rpl_f32(const KMeansArgs& a, int32_t dim, hipStream_t stream);
 bool launch_kmeans16_rpl_f16(const KMeansArgs& a, int32_t dim, hipStream_t stream);
+bool launch_kmeans16_rpl_tail_f32(const KMeansArgs& a, int32_t dim, hipStream_t stream);
+bool launch_kmeans16_rpl_tail_f16(const KMeansArgs& a, int32_t dim, hipStream_t stream);
 
 // Any dimension: one row per lane, elements re-read from memory in every round.
 template <typename Tin>
@@ -72,7 +74,8 @@ __global__ void __launch_bounds__(64) kmeans16_any_kernel(KMeansArgs a, int32_t 
 
 hipError_t launch_kmeans16(const KMeansArgs& a, int dtype, int32_t dim, hipStream_t stream)
 {
-    const bool done = dtype == 0 ? launch_kmeans16_rpl_f32(a, dim, stream) : launch_kmeans16_rpl_f16(a, dim, stream);
+    bool done = dtype == 0 ? launch_kmeans16_rpl_f32(a, dim, stream) : launch_kmeans16_rpl_f16(a, dim, stream);
+    if (!done) done = dtype == 0 ? launch_kmeans16_rpl_tail_f32(a, dim, stream) : launch_kmeans16_rpl_tail_f16(a, dim, stream);
     if (!done) {
         const dim3 grid((unsigned)((a.rows + 63) / 64)), block(64);
         if (dtype == 0)

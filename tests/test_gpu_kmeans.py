@@ -73,6 +73,17 @@ def test_other_dimensions(e4q, oracle_lib, dim, dtype):
     compare(e4q, oracle_lib, t, 6, f"any dim={dim}")
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.float16])
+@pytest.mark.parametrize("dim", [17, 19, 23, 25, 39, 50, 57, 71, 100, 121, 127])
+def test_masked_tail_dimensions(e4q, oracle_lib, dim, dtype):
+    """16 < dim < 128, not a multiple of 8: the register-resident kernel of the next multiple of 8 with a
+    masked tail, several waves and a ragged last one; rows of (dim + 1) / 2 bytes, dense."""
+    from paper_1911_02079_amd import synth
+
+    t = synth.mixture_table(64 * 40 + 13, dim, seed=800 + dim, device="cuda").to(dtype)
+    compare(e4q, oracle_lib, t, 9, f"masked tail dim={dim}")
+
+
 @pytest.mark.parametrize("iters", [0, 1, 2, 7, 40])
 def test_round_counts(e4q, oracle_lib, iters):
     from paper_1911_02079_amd import synth
@@ -137,7 +148,7 @@ def clumped_rows(rows, dim, seed):
     return out
 
 
-@pytest.mark.parametrize("dim", [24, 64, 128])
+@pytest.mark.parametrize("dim", [24, 50, 64, 101, 128])
 def test_clumped_rows_and_forced_scan(e4q, oracle_lib, dim, monkeypatch):
     """The bisection over ordered centres and the 16-centre scan give the oracle's result on rows with
     coinciding and nearly coinciding centres; the scan is forced through the diagnostic switch."""

@@ -60,6 +60,45 @@ __global__ void __launch_bounds__(kDqBlock) dequantize_any_kernel(const uint8_t*
     }
 }
 
+// Any dim, out 16-byte aligned: one thread per four consecutive elements of the flattened output (they
+// may straddle a row boundary), one 16-byte store per lane.  The row and column of the first element
+// cost one division (32-bit unless the table has 2^32 elements or more); the others follow by stepping.
+template <bool WIDE>
+__global__ void __launch_bounds__(kDqBlock) dequantize_flat4_kernel(const uint8_t* __restrict__ codes,
+                                                                   const uint16_t* __restrict__ scale_f16,
+                                                                   const uint16_t* __restrict__ bias_f16,
+                                                                   int64_t n_elems, uint32_t dim, uint32_t nbits,
+                                                                   float* __restrict__ out)
+{
+    const int64_t e0 = ((int64_t)blockIdx.x * kDqBlock + threadIdx.x) * 4;
+    if (e0 >= n_elems) return;
+    const uint32_t per = 8 / nbits;
+    const uint32_t nbytes = (dim + per - 1) / per;
+    const uint32_t mask = (1u << nbits) - 1u;
+    int64_t row = WIDE ? e0 / dim : (int64_t)((uint32_t)e0 / dim);
+    uint32_t k = (uint32_t)(e0 - row * dim);
+    float v[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        v[j] = 0.0f;
+        if (e0 + j < n_elems) {
+            const uint32_t byte = codes[row * nbytes + k / per];
+            const uint32_t q = (byte >> ((k % per) * nbits)) & mask;
+            v[j] = __builtin_fmaf((float)q, f16_bits_to_float(scale_f16[row]), f16_bits_to_float(bias_f16[row]));
+        }
+        if (++k == dim) {
+            k = 0;
+            ++row;
+        }
+    }
+    if (e0 + 4 <= n_elems) {
+        floatx4 o = {v[0], v[1], v[2], v[3]};
+        __builtin_nontemporal_store(o, reinterpret_cast<floatx4*>(out + e0));
+    } else {
+        for (int j = 0; e0 + j < n_elems; ++j) out[e0 + j] = v[j];
+    }
+}
+
 template <int NBITS>
 static void launch_w4(const void* codes, const uint16_t* scale_f16, const uint16_t* bias_f16, int64_t n_quads,
                       uint32_t quads_per_row, floatx4* out, hipStream_t stream)
@@ -89,10 +128,20 @@ hipError_t launch_dequantize(const uint8_t* codes, const uint16_t* scale_f16, co
         else launch_w4<2>(codes, scale_f16, bias_f16, n_quads, qpr, o4, stream);
     } else {
         const int64_t n_elems = rows * dim;
-        int64_t blocks = (n_elems + kDqBlock - 1) / kDqBlock;
-        if (blocks > 0x7fffffffLL) blocks = 0x7fffffffLL;  // the kernel loops over what is left
-        hipLaunchKernelGGL(dequantize_any_kernel, dim3((unsigned)blocks), dim3(kDqBlock), 0, stream, codes,
-                           scale_f16, bias_f16, n_elems, (uint32_t)dim, (uint32_t)nbits, out);
+        const int64_t blocks4 = ((n_elems + 3) / 4 + kDqBlock - 1) / kDqBlock;
+        if (reinterpret_cast<uintptr_t>(out) % 16 == 0 && blocks4 <= 0x7fffffffLL) {
+            if (n_elems > 0xffffffffLL)
+                hipLaunchKernelGGL(dequantize_flat4_kernel<true>, dim3((unsigned)blocks4), dim3(kDqBlock), 0, stream,
+                                   codes, scale_f16, bias_f16, n_elems, (uint32_t)dim, (uint32_t)nbits, out);
+            else
+                hipLaunchKernelGGL(dequantize_flat4_kernel<false>, dim3((unsigned)blocks4), dim3(kDqBlock), 0, stream,
+                                   codes, scale_f16, bias_f16, n_elems, (uint32_t)dim, (uint32_t)nbits, out);
+        } else {
+            int64_t blocks = (n_elems + kDqBlock - 1) / kDqBlock;
+            if (blocks > 0x7fffffffLL) blocks = 0x7fffffffLL;  // the kernel loops over what is left
+            hipLaunchKernelGGL(dequantize_any_kernel, dim3((unsigned)blocks), dim3(kDqBlock), 0, stream, codes,
+                               scale_f16, bias_f16, n_elems, (uint32_t)dim, (uint32_t)nbits, out);
+        }
     }
     return hipGetLastError();
 }

@@ -126,6 +126,41 @@ __global__ void __launch_bounds__(kCbBlock) dequantize_codebook_any_kernel(const
     }
 }
 
+// Any dim, out 16-byte aligned: four consecutive elements of the flattened output per thread (they may
+// straddle a row boundary), one 16-byte store per lane, one division per thread.
+template <bool WIDE>
+__global__ void __launch_bounds__(kCbBlock) dequantize_codebook_flat4_kernel(const uint8_t* __restrict__ idx,
+                                                                             const uint16_t* __restrict__ cb,
+                                                                             int64_t n_elems, uint32_t dim,
+                                                                             float* __restrict__ out)
+{
+    const int64_t e0 = ((int64_t)blockIdx.x * kCbBlock + threadIdx.x) * 4;
+    if (e0 >= n_elems) return;
+    const uint32_t nbytes = (dim + 1) / 2;
+    int64_t row = WIDE ? e0 / dim : (int64_t)((uint32_t)e0 / dim);
+    uint32_t k = (uint32_t)(e0 - row * dim);
+    float v[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        v[j] = 0.0f;
+        if (e0 + j < n_elems) {
+            const uint32_t byte = idx[row * nbytes + k / 2];
+            const uint32_t q = (k & 1u) ? (byte >> 4) : (byte & 15u);
+            v[j] = f16_bits_to_float(cb[row * kK + q]);
+        }
+        if (++k == dim) {
+            k = 0;
+            ++row;
+        }
+    }
+    if (e0 + 4 <= n_elems) {
+        floatx4 o = {v[0], v[1], v[2], v[3]};
+        __builtin_nontemporal_store(o, reinterpret_cast<floatx4*>(out + e0));
+    } else {
+        for (int j = 0; e0 + j < n_elems; ++j) out[e0 + j] = v[j];
+    }
+}
+
 hipError_t launch_dequantize_codebook(const uint8_t* idx, const uint16_t* centroids_f16, int64_t rows,
                                       int32_t dim, float* out, hipStream_t stream)
 {
@@ -139,10 +174,20 @@ hipError_t launch_dequantize_codebook(const uint8_t* idx, const uint16_t* centro
                            reinterpret_cast<floatx4*>(out));
     } else {
         const int64_t n_elems = rows * dim;
-        int64_t blocks = (n_elems + kCbBlock - 1) / kCbBlock;
-        if (blocks > 0x7fffffffLL) blocks = 0x7fffffffLL;  // the kernel loops over what is left
-        hipLaunchKernelGGL(dequantize_codebook_any_kernel, dim3((unsigned)blocks), dim3(kCbBlock), 0, stream, idx,
-                           centroids_f16, n_elems, (uint32_t)dim, out);
+        const int64_t blocks4 = ((n_elems + 3) / 4 + kCbBlock - 1) / kCbBlock;
+        if (reinterpret_cast<uintptr_t>(out) % 16 == 0 && blocks4 <= 0x7fffffffLL) {
+            if (n_elems > 0xffffffffLL)
+                hipLaunchKernelGGL(dequantize_codebook_flat4_kernel<true>, dim3((unsigned)blocks4), dim3(kCbBlock), 0,
+                                   stream, idx, centroids_f16, n_elems, (uint32_t)dim, out);
+            else
+                hipLaunchKernelGGL(dequantize_codebook_flat4_kernel<false>, dim3((unsigned)blocks4), dim3(kCbBlock), 0,
+                                   stream, idx, centroids_f16, n_elems, (uint32_t)dim, out);
+        } else {
+            int64_t blocks = (n_elems + kCbBlock - 1) / kCbBlock;
+            if (blocks > 0x7fffffffLL) blocks = 0x7fffffffLL;  // the kernel loops over what is left
+            hipLaunchKernelGGL(dequantize_codebook_any_kernel, dim3((unsigned)blocks), dim3(kCbBlock), 0, stream, idx,
+                               centroids_f16, n_elems, (uint32_t)dim, out);
+        }
     }
     return hipGetLastError();
 }

@@ -322,6 +322,41 @@ def test_strided_and_unaligned_views(e4q, oracle_lib):
     assert np.array_equal(xh.cpu().numpy(), oracle_lib.dequantize(o[0], o[1], o[2], dim))
 
 
+@pytest.mark.parametrize("nbits", [2, 4, 8])
+@pytest.mark.parametrize("dim", [1, 3, 7, 13, 50, 101, 127, 130])
+def test_dequantize_odd_dimensions_aligned_and_not(e4q, oracle_lib, dim, nbits):
+    """dim % 4 != 0: four flattened elements per thread into a 16-byte aligned output (groups straddle row
+    boundaries, the last group is partial), one element per thread into an output that is not; and an odd
+    dimension of the masked-tail quantizer written into a code buffer that is 4-byte aligned only."""
+    from paper_1911_02079_amd import synth
+
+    rows = 64 * 9 + 5
+    t = synth.gaussian_table(rows, dim, 0.1, seed=7100 + dim, device="cuda")
+    codes, scale, bias = e4q.quantize_rowwise_greedy(t, 30, 0.2, nbits=nbits)
+    torch.cuda.synchronize()
+    o = oracle_lib.quantize_rowwise_greedy(t.cpu().numpy(), 30, 0.2, nbits=nbits)
+    assert np.array_equal(codes.cpu().numpy(), o[0])
+    want = oracle_lib.dequantize(o[0], o[1], o[2], dim, nbits=nbits)
+    say(f"dequantize dim={dim} nbits={nbits}, aligned output")
+    xh = e4q.dequantize(codes, scale, bias, dim, nbits=nbits)
+    torch.cuda.synchronize()
+    assert xh.data_ptr() % 16 == 0 and np.array_equal(xh.cpu().numpy(), want)
+    say(f"dequantize dim={dim} nbits={nbits}, output offset by 4 bytes")
+    buf = torch.full((rows * dim + 2,), -7.0, device="cuda")
+    e4q.dequantize(codes, scale, bias, dim, nbits=nbits, out=buf[1:-1].reshape(rows, dim))
+    torch.cuda.synchronize()
+    assert np.array_equal(buf[1:-1].reshape(rows, dim).cpu().numpy(), want)
+    assert float(buf[0]) == -7.0 and float(buf[-1]) == -7.0
+    say(f"quantize dim={dim} nbits={nbits} into a code buffer offset by 4 bytes")
+    nbytes = codes.shape[1]
+    cbuf = torch.full((rows * nbytes + 8,), 0xAB, dtype=torch.uint8, device="cuda")
+    out = (cbuf[4:-4].reshape(rows, nbytes), torch.empty_like(scale), torch.empty_like(bias))
+    e4q.quantize_rowwise_greedy(t, 30, 0.2, nbits=nbits, out=out)
+    torch.cuda.synchronize()
+    assert np.array_equal(out[0].cpu().numpy(), o[0])
+    assert bool((cbuf[:4] == 0xAB).all()) and bool((cbuf[-4:] == 0xAB).all())
+
+
 def test_outputs_do_not_overrun(e4q):
     """Guard bands around the outputs stay untouched (ragged row count, fast and fallback paths)."""
     from paper_1911_02079_amd import synth

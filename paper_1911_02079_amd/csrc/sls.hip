@@ -82,32 +82,101 @@ __global__ void __launch_bounds__(kSlsBlock) sls_w8_kernel(const uint32_t* __res
     out[2 * t + 1] = v1;
 }
 
-// Any dim and alignment: one thread per output element.
-template <typename Tidx>
-__global__ void __launch_bounds__(kSlsBlock) sls_any_kernel(const uint8_t* __restrict__ codes,
-                                                            const uint16_t* __restrict__ sc,
-                                                            const uint16_t* __restrict__ bi, int64_t rows,
-                                                            uint32_t dim, const Tidx* __restrict__ indices,
-                                                            int64_t n_indices, const int64_t* __restrict__ offsets,
-                                                            int64_t n_bags, float* __restrict__ out)
+// Any dim, pitch and alignment, 8 elements per thread: the loop shared by the two kernels below.
+// `gather(r)` returns code word `word` of row r (bytes beyond the row's codes read as 0) and its
+// parameters, all zero for an index outside the table.  Only the elements that exist are stored.
+template <typename Tidx, class Gather>
+__device__ __forceinline__ void sls_bytes_body(Gather&& gather, uint32_t dim, uint32_t word,
+                                               const Tidx* __restrict__ indices, int64_t n_indices,
+                                               const int64_t* __restrict__ offsets, int64_t bag,
+                                               float* __restrict__ out)
 {
-    const int64_t t = (int64_t)blockIdx.x * kSlsBlock + threadIdx.x;
-    const int64_t bag = t / dim;
-    if (bag >= n_bags) return;
-    const uint32_t k = (uint32_t)(t - bag * dim);
-    const uint32_t nbytes = (dim + 1) / 2;
     const int64_t lo = offsets[bag], hi = offsets[bag + 1];
     const int64_t begin = lo < 0 ? 0 : (lo > n_indices ? n_indices : lo);
     const int64_t end = hi < begin ? begin : (hi > n_indices ? n_indices : hi);
-    float acc = 0.0f;
-    for (int64_t i = begin; i < end; ++i) {
-        const int64_t r = (int64_t)indices[i];
-        if (r < 0 || r >= rows) continue;
-        const uint32_t byte = codes[r * nbytes + k / 2];
-        const uint32_t q = (k & 1u) ? (byte >> 4) : (byte & 15u);
-        acc = acc + __builtin_fmaf((float)q, f16_bits_to_float(sc[r]), f16_bits_to_float(bi[r]));
+    float acc[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
+    int64_t i = begin;
+    for (; i + 4 <= end; i += 4) {
+        const Tidx i0 = indices[i], i1 = indices[i + 1], i2 = indices[i + 2], i3 = indices[i + 3];
+        const SlsRow g0 = gather((int64_t)i0), g1 = gather((int64_t)i1), g2 = gather((int64_t)i2), g3 = gather((int64_t)i3);
+        sls_add_word(acc, g0.c, g0.s, g0.b);
+        sls_add_word(acc, g1.c, g1.s, g1.b);
+        sls_add_word(acc, g2.c, g2.s, g2.b);
+        sls_add_word(acc, g3.c, g3.s, g3.b);
     }
-    out[t] = acc;
+    for (; i < end; ++i) {
+        const SlsRow g = gather((int64_t)indices[i]);
+        sls_add_word(acc, g.c, g.s, g.b);
+    }
+    float* o = out + bag * dim + 8 * word;
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+        if (8 * word + e < dim) o[e] = acc[e];
+}
+
+// Reads up to four code bytes at p (those below `limit` bytes from the row start at offset `at`).
+__device__ __forceinline__ uint32_t sls_code_bytes(const uint8_t* __restrict__ p, uint32_t at, uint32_t limit)
+{
+    uint32_t c = 0;
+#pragma unroll
+    for (uint32_t j = 0; j < 4; ++j)
+        if (at + j < limit) c |= (uint32_t)p[at + j] << (8 * j);
+    return c;
+}
+
+// Separate arrays, any dim and alignment: one thread per 8 output elements, byte reads.
+template <typename Tidx>
+__global__ void __launch_bounds__(kSlsBlock) sls_bytes_kernel(const uint8_t* __restrict__ codes,
+                                                              const uint16_t* __restrict__ sc,
+                                                              const uint16_t* __restrict__ bi, int64_t rows,
+                                                              uint32_t dim, const Tidx* __restrict__ indices,
+                                                              int64_t n_indices, const int64_t* __restrict__ offsets,
+                                                              int64_t n_bags, float* __restrict__ out)
+{
+    const uint32_t wpr = (dim + 7) / 8, nbytes = (dim + 1) / 2;
+    const int64_t t = (int64_t)blockIdx.x * kSlsBlock + threadIdx.x;
+    const int64_t bag = t / wpr;
+    if (bag >= n_bags) return;
+    const uint32_t word = (uint32_t)(t - bag * wpr);
+    sls_bytes_body<Tidx>([&](int64_t r) {
+        SlsRow g = {0u, 0.0f, 0.0f};
+        if (r >= 0 && r < rows) {
+            g.c = sls_code_bytes(codes + r * nbytes, 4 * word, nbytes);
+            g.s = f16_bits_to_float(sc[r]);
+            g.b = f16_bits_to_float(bi[r]);
+        }
+        return g;
+    }, dim, word, indices, n_indices, offsets, bag, out);
+}
+
+// Fused records, any dim and pitch: one thread per 8 output elements, 2-byte reads (records are 2-byte
+// aligned: the buffer is, and the pitch is even; so are a record's code words and its parameters).
+template <typename Tidx>
+__global__ void __launch_bounds__(kSlsBlock) sls_fused_h8_kernel(const uint8_t* __restrict__ fused, int64_t rows,
+                                                                 uint32_t dim, int64_t pitch,
+                                                                 const Tidx* __restrict__ indices, int64_t n_indices,
+                                                                 const int64_t* __restrict__ offsets, int64_t n_bags,
+                                                                 float* __restrict__ out)
+{
+    const uint32_t wpr = (dim + 7) / 8, nbytes = (dim + 1) / 2;
+    const uint32_t params_at = (nbytes + 1u) & ~1u;
+    const int64_t t = (int64_t)blockIdx.x * kSlsBlock + threadIdx.x;
+    const int64_t bag = t / wpr;
+    if (bag >= n_bags) return;
+    const uint32_t word = (uint32_t)(t - bag * wpr);
+    sls_bytes_body<Tidx>([&](int64_t r) {
+        SlsRow g = {0u, 0.0f, 0.0f};
+        if (r >= 0 && r < rows) {
+            // both halves of the word lie inside the record (its parameters follow the codes)
+            const uint16_t* h = reinterpret_cast<const uint16_t*>(fused + r * pitch);
+            const uint32_t c = (uint32_t)h[2 * word] | ((uint32_t)h[2 * word + 1] << 16);
+            const uint32_t valid = nbytes - 4 * word;  // code bytes in this word, if fewer than 4
+            g.c = valid >= 4 ? c : (c & ((1u << (8 * valid)) - 1u));
+            g.s = f16_bits_to_float(h[params_at / 2]);
+            g.b = f16_bits_to_float(h[params_at / 2 + 1]);
+        }
+        return g;
+    }, dim, word, indices, n_indices, offsets, bag, out);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -240,36 +309,6 @@ __global__ void __launch_bounds__(kSlsBlock) sls_fused_w8_kernel(const uint32_t*
     }
 }
 
-// Lookup over fused records, any dim / pitch / alignment: one thread per output element.
-template <typename Tidx>
-__global__ void __launch_bounds__(kSlsBlock) sls_fused_any_kernel(const uint8_t* __restrict__ fused, int64_t rows,
-                                                                  uint32_t dim, int64_t pitch,
-                                                                  const Tidx* __restrict__ indices, int64_t n_indices,
-                                                                  const int64_t* __restrict__ offsets, int64_t n_bags,
-                                                                  float* __restrict__ out)
-{
-    const int64_t t = (int64_t)blockIdx.x * kSlsBlock + threadIdx.x;
-    const int64_t bag = t / dim;
-    if (bag >= n_bags) return;
-    const uint32_t k = (uint32_t)(t - bag * dim);
-    const uint32_t params_at = (((dim + 1) / 2) + 1u) & ~1u;
-    const int64_t lo = offsets[bag], hi = offsets[bag + 1];
-    const int64_t begin = lo < 0 ? 0 : (lo > n_indices ? n_indices : lo);
-    const int64_t end = hi < begin ? begin : (hi > n_indices ? n_indices : hi);
-    float acc = 0.0f;
-    for (int64_t i = begin; i < end; ++i) {
-        const int64_t r = (int64_t)indices[i];
-        if (r < 0 || r >= rows) continue;
-        const uint8_t* rec = fused + r * pitch;
-        const uint32_t byte = rec[k / 2];
-        const uint32_t q = (k & 1u) ? (byte >> 4) : (byte & 15u);
-        const uint16_t sbits = (uint16_t)(rec[params_at] | (rec[params_at + 1] << 8));
-        const uint16_t bbits = (uint16_t)(rec[params_at + 2] | (rec[params_at + 3] << 8));
-        acc = acc + __builtin_fmaf((float)q, f16_bits_to_float(sbits), f16_bits_to_float(bbits));
-    }
-    out[t] = acc;
-}
-
 template <typename Tidx>
 static hipError_t launch_sls_fused_t(const uint8_t* fused, int64_t rows, int32_t dim, int64_t pitch,
                                      const void* indices, int64_t n_indices, const int64_t* offsets, int64_t n_bags,
@@ -282,7 +321,7 @@ static hipError_t launch_sls_fused_t(const uint8_t* fused, int64_t rows, int32_t
     if (fast) {
         wpt = wpr % 2 == 0 ? 2 : 1;  // 8-byte gathers measured 6 % faster than 4-byte ones, 16-byte ones no better
     }
-    const int64_t threads = fast ? n_bags * (wpr / wpt) : n_bags * dim;
+    const int64_t threads = fast ? n_bags * (wpr / wpt) : n_bags * ((dim + 7) / 8);
     const int64_t blocks = (threads + kSlsBlock - 1) / kSlsBlock;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     const dim3 grid((unsigned)blocks), block(kSlsBlock);
@@ -290,7 +329,7 @@ static hipError_t launch_sls_fused_t(const uint8_t* fused, int64_t rows, int32_t
     const Tidx* idx = static_cast<const Tidx*>(indices);
     floatx4* o4 = reinterpret_cast<floatx4*>(out);
     if (!fast)
-        hipLaunchKernelGGL(sls_fused_any_kernel<Tidx>, grid, block, 0, stream, fused, rows, (uint32_t)dim, pitch, idx,
+        hipLaunchKernelGGL(sls_fused_h8_kernel<Tidx>, grid, block, 0, stream, fused, rows, (uint32_t)dim, pitch, idx,
                            n_indices, offsets, n_bags, out);
     else if (wpt == 2)
         hipLaunchKernelGGL((sls_fused_w8_kernel<Tidx, 2>), grid, block, 0, stream, f32, rows, (uint32_t)wpr,
@@ -317,7 +356,7 @@ static hipError_t launch_sls_t(const uint8_t* codes, const uint16_t* sc, const u
 {
     const bool fast = dim % 8 == 0 && reinterpret_cast<uintptr_t>(codes) % 4 == 0 &&
                       reinterpret_cast<uintptr_t>(out) % 16 == 0;
-    const int64_t threads = fast ? n_bags * (dim / 8) : n_bags * dim;
+    const int64_t threads = fast ? n_bags * (dim / 8) : n_bags * ((dim + 7) / 8);
     const int64_t blocks = (threads + kSlsBlock - 1) / kSlsBlock;
     if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     if (fast)
@@ -326,7 +365,7 @@ static hipError_t launch_sls_t(const uint8_t* codes, const uint16_t* sc, const u
                            static_cast<const Tidx*>(indices), n_indices, offsets, n_bags,
                            reinterpret_cast<floatx4*>(out));
     else
-        hipLaunchKernelGGL(sls_any_kernel<Tidx>, dim3((unsigned)blocks), dim3(kSlsBlock), 0, stream, codes, sc, bi,
+        hipLaunchKernelGGL(sls_bytes_kernel<Tidx>, dim3((unsigned)blocks), dim3(kSlsBlock), 0, stream, codes, sc, bi,
                            rows, (uint32_t)dim, static_cast<const Tidx*>(indices), n_indices, offsets, n_bags, out);
     return hipGetLastError();
 }

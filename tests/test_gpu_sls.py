@@ -59,7 +59,7 @@ def check(e4q, oracle, table, indices, offsets, idx_dtype, label):
 
 
 @pytest.mark.parametrize("idx_dtype", [torch.int64, torch.int32])
-@pytest.mark.parametrize("dim", [8, 24, 64, 128, 256, 13, 100, 1])
+@pytest.mark.parametrize("dim", [8, 24, 64, 128, 256, 13, 100, 1, 7, 50, 127, 130])
 def test_random_bags(e4q, oracle_lib, dim, idx_dtype):
     from paper_1911_02079_amd import synth
 

@@ -7,14 +7,17 @@
 // identical to the one-row-per-lane kernels.  All L lanes of a group end up with the same sums and
 // take the same decisions.
 //
-// Used where one row per lane is the wrong shape:
+// Used where one row per lane is the wrong shape (the host weighs the layouts by a cost model):
 //   * few rows (rows/64 waves would leave most of the chip idle): E = 8 spreads a row over up to
 //     64 lanes;
+//   * tables of a few waves per SIMD: E = 16, 32 or 64 gives every SIMD several waves to interleave,
+//     which a lone wave per SIMD cannot make up for (it issues only every fifth cycle);
 //   * ratio == 0 (plain min/max quantization, bound by HBM): with E = 8 a wave reads and writes
 //     contiguous memory;
-//   * dimensions above 128 or not a multiple of 8: E = 128 keeps the per-range scalar work (two
-//     divisions, two binary16 round trips, ~45 instructions that every lane of the group repeats)
-//     small against 8 operations for each of 128 elements.
+//   * dimensions above 128: E = 128 keeps the per-range scalar work (two divisions, two binary16
+//     round trips, ~45 instructions that every lane of the group repeats) small against 8
+//     operations for each of 128 elements; E <= 32 if the dimension is not a multiple of 8 (every
+//     element then carries a lane mask, and 32 of them are what the scalar registers hold).
 // Masked instantiations take any dim <= E*L: elements at or beyond dim contribute exactly +0 to
 // the sums and are kept out of min/max.  MASK = 0: dim == E*L, no masking; MASK = 1: dim is a
 // multiple of 8, one select per block of 8 elements; MASK = 2: any dim, one select per element.

@@ -72,16 +72,135 @@ __global__ void __launch_bounds__(64) kmeans16_any_kernel(KMeansArgs a, int32_t 
     }
 }
 
+// Dimensions above 128: one row per lane, 64 elements of it in registers at a time.  Every round walks
+// the row chunk by chunk (16-byte loads where the table allows them), so a cluster's sum still grows
+// in element order; the per-element work is the register-resident kernels' (bisection over ordered
+// centres, scan otherwise).  A row is read 2 + lloyd_iters times instead of once; those reads mostly
+// hit the caches and the path stays bound by VALU issue.
+constexpr int kChunk = 64;
+
+template <typename Tin>
+__device__ __forceinline__ void load_chunk(const Tin* __restrict__ src, int n, bool vec, float (&x)[kChunk])
+{
+    if (n == kChunk) {
+        load_row<kChunk>(src, vec, x);
+    } else {
+#pragma unroll
+        for (int k = 0; k < kChunk; ++k) x[k] = (float)src[k < n ? k : 0];
+    }
+}
+
+template <typename Tin>
+__global__ void __launch_bounds__(64) kmeans16_chunk_kernel(KMeansArgs a, int32_t d)
+{
+    __shared__ LloydScratch scratch;
+    const int lane = threadIdx.x;
+    const int64_t row = (int64_t)blockIdx.x * 64 + lane;
+    const bool live = row < a.rows;
+    const int64_t r = live ? row : a.rows - 1;  // tail lanes redo the last row and store nothing
+    const Tin* src = static_cast<const Tin*>(a.table) + r * a.row_stride;
+    // chunk starts are multiples of 64 elements, so they keep the row's 16-byte alignment
+    const bool vec = a.vec_loads != 0;
+    float x[kChunk];
+
+    float lo = (float)src[0], hi = lo;
+    for (int c0 = 0; c0 < d; c0 += kChunk) {
+        const int n = d - c0 < kChunk ? d - c0 : kChunk;
+        load_chunk(src + c0, n, vec, x);  // registers beyond n copy the chunk's first element
+#pragma unroll
+        for (int k = 0; k < kChunk; ++k) {
+            lo = __builtin_fminf(lo, x[k]);
+            hi = __builtin_fmaxf(hi, x[k]);
+        }
+    }
+    float c[kK];
+    grid_centres(lo, hi, c);
+
+    for (int it = 0; it < a.lloyd_iters; ++it) {
+        lloyd_clear(scratch, lane);
+        if (!a.force_scan && wave_centres_sorted(c)) {
+            for (int c0 = 0; c0 < d; c0 += kChunk) {
+                const int n = d - c0 < kChunk ? d - c0 : kChunk;
+                load_chunk(src + c0, n, vec, x);
+#pragma unroll
+                for (int e = 0; e < kChunk; ++e)
+                    if (e < n) lloyd_add(scratch, lane, nearest_centre_sorted(x[e], c), x[e]);  // scalar branch
+            }
+        } else {
+#pragma unroll 1
+            for (int e = 0; e < d; ++e) {
+                const float v = (float)src[e];
+                lloyd_add(scratch, lane, nearest_centre(v, c), v);
+            }
+        }
+        lloyd_update(scratch, lane, c);
+    }
+
+    float ch[kK];
+#pragma unroll
+    for (int k = 0; k < kK; ++k) ch[k] = through_f16(c[k]);
+    if (live) store_codebook(c, a.centroids_f16 + row * kK);
+    const int nbytes = (d + 1) / 2;
+    uint8_t* out = a.idx + row * nbytes;
+    if (a.force_scan || !wave_centres_sorted(ch)) {
+        if (live) {
+#pragma unroll 1
+            for (int b = 0; b < nbytes; ++b) {
+                const uint32_t q0 = (uint32_t)nearest_centre((float)src[2 * b], ch);
+                const uint32_t q1 = (2 * b + 1 < d) ? (uint32_t)nearest_centre((float)src[2 * b + 1], ch) : 0u;
+                out[b] = (uint8_t)(q0 | (q1 << 4));
+            }
+        }
+        return;
+    }
+    // word stores need 4-byte aligned rows: a 4-byte aligned buffer and a row size of 4k bytes
+    const bool words = a.vec_stores >= 1 && nbytes % 4 == 0;
+    for (int c0 = 0; c0 < d; c0 += kChunk) {
+        const int n = d - c0 < kChunk ? d - c0 : kChunk;
+        load_chunk(src + c0, n, vec, x);
+        uint32_t w[kChunk / 8];
+#pragma unroll
+        for (int i = 0; i < kChunk / 8; ++i) {
+            uint32_t acc = 0;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const uint32_t q = (uint32_t)nearest_centre_sorted(x[8 * i + e], ch);
+                acc |= (8 * i + e < n ? q : 0u) << (4 * e);
+            }
+            w[i] = acc;
+        }
+        if (!live) continue;
+        const int chunk_bytes = (n + 1) / 2;
+        uint8_t* o = out + c0 / 2;
+        if (words && chunk_bytes % 4 == 0) {
+#pragma unroll
+            for (int i = 0; i < kChunk / 8; ++i)
+                if (4 * i < chunk_bytes) reinterpret_cast<uint32_t*>(o)[i] = w[i];
+        } else {
+#pragma unroll
+            for (int b = 0; b < kChunk / 2; ++b)
+                if (b < chunk_bytes) o[b] = (uint8_t)(w[b / 4] >> (8 * (b % 4)));
+        }
+    }
+}
+
 hipError_t launch_kmeans16(const KMeansArgs& a, int dtype, int32_t dim, hipStream_t stream)
 {
     bool done = dtype == 0 ? launch_kmeans16_rpl_f32(a, dim, stream) : launch_kmeans16_rpl_f16(a, dim, stream);
     if (!done) done = dtype == 0 ? launch_kmeans16_rpl_tail_f32(a, dim, stream) : launch_kmeans16_rpl_tail_f16(a, dim, stream);
     if (!done) {
         const dim3 grid((unsigned)((a.rows + 63) / 64)), block(64);
-        if (dtype == 0)
-            hipLaunchKernelGGL(kmeans16_any_kernel<float>, grid, block, 0, stream, a, dim);
-        else
-            hipLaunchKernelGGL(kmeans16_any_kernel<_Float16>, grid, block, 0, stream, a, dim);
+        if (dim > 128) {
+            if (dtype == 0)
+                hipLaunchKernelGGL(kmeans16_chunk_kernel<float>, grid, block, 0, stream, a, dim);
+            else
+                hipLaunchKernelGGL(kmeans16_chunk_kernel<_Float16>, grid, block, 0, stream, a, dim);
+        } else {  // dim <= 16: a conversion
+            if (dtype == 0)
+                hipLaunchKernelGGL(kmeans16_any_kernel<float>, grid, block, 0, stream, a, dim);
+            else
+                hipLaunchKernelGGL(kmeans16_any_kernel<_Float16>, grid, block, 0, stream, a, dim);
+        }
     }
     return hipGetLastError();
 }

@@ -84,6 +84,18 @@ def test_masked_tail_dimensions(e4q, oracle_lib, dim, dtype):
     compare(e4q, oracle_lib, t, 9, f"masked tail dim={dim}")
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.float16])
+@pytest.mark.parametrize("dim", [129, 136, 192, 200, 256, 333, 1000, 4096])
+def test_dimensions_above_128(e4q, oracle_lib, dim, dtype):
+    """Rows that do not fit the register file are walked 64 elements at a time (whole and partial chunks,
+    word and byte stores), several waves and a ragged last one."""
+    from paper_1911_02079_amd import synth
+
+    rows = 64 * 5 + 3 if dim <= 1000 else 67
+    t = synth.mixture_table(rows, dim, seed=900 + dim, device="cuda").to(dtype)
+    compare(e4q, oracle_lib, t, 7, f"chunked dim={dim}")
+
+
 @pytest.mark.parametrize("iters", [0, 1, 2, 7, 40])
 def test_round_counts(e4q, oracle_lib, iters):
     from paper_1911_02079_amd import synth
@@ -148,7 +160,7 @@ def clumped_rows(rows, dim, seed):
     return out
 
 
-@pytest.mark.parametrize("dim", [24, 50, 64, 101, 128])
+@pytest.mark.parametrize("dim", [24, 50, 64, 101, 128, 200])
 def test_clumped_rows_and_forced_scan(e4q, oracle_lib, dim, monkeypatch):
     """The bisection over ordered centres and the 16-centre scan give the oracle's result on rows with
     coinciding and nearly coinciding centres; the scan is forced through the diagnostic switch."""

@@ -387,6 +387,38 @@ def test_non_finite_rows_do_not_disturb_their_neighbours(e4q, oracle_lib, dim):
     assert np.array_equal(idx[good].cpu().numpy(), k[0]) and np.array_equal(f16_bits(cent[good]), k[1])
 
 
+def random_shapes(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        dim = int(rng.choice([rng.integers(1, 17), rng.integers(17, 129), rng.integers(129, 400), 8 * rng.integers(1, 17)]))
+        rows = int(10 ** rng.uniform(2.0, 5.8))
+        rows = min(rows, 12_000_000 // dim)
+        out.append((rows, dim, bool(rng.integers(0, 2)), int(rng.choice([2, 4, 4, 4, 8])), int(rng.integers(3, 40)),
+                    float(np.float32(rng.uniform(0.05, 0.6)))))
+    return out
+
+
+@pytest.mark.parametrize("rows,dim,half,nbits,n_bins,ratio", random_shapes(64, 20261127))
+def test_random_shapes(e4q, oracle_lib, rows, dim, half, nbits, n_bins, ratio):
+    """Seeded random (rows, dim, input type, code width, search setting): whatever layout the host picks for
+    the shape, every row matches the oracle, and the de-quantizer matches on the emitted artefacts."""
+    from helpers import oracle_rows_in_parallel
+    from paper_1911_02079_amd import synth
+
+    t = synth.outlier_table(rows, dim, seed=rows + dim, device="cuda")
+    if half:
+        t = t.half()
+    say(f"random shape rows={rows} dim={dim} half={half} nbits={nbits} b={n_bins} r={ratio:.3f}")
+    codes, scale, bias = e4q.quantize_rowwise_greedy(t, n_bins, ratio, nbits=nbits)
+    xh = e4q.dequantize(codes, scale, bias, dim, nbits=nbits)
+    torch.cuda.synchronize()
+    o = oracle_rows_in_parallel(oracle_lib, t.cpu().numpy(), n_bins, ratio, nbits=nbits)
+    bad = np.flatnonzero((codes.cpu().numpy() != o[0]).any(axis=1) | (f16_bits(scale) != o[1]) | (f16_bits(bias) != o[2]))
+    assert bad.size == 0, f"{bad.size} rows differ, first {bad[:5]}"
+    assert np.array_equal(xh.cpu().numpy(), oracle_lib.dequantize(o[0], o[1], o[2], dim, nbits=nbits))
+
+
 def test_outputs_do_not_overrun(e4q):
     """Guard bands around the outputs stay untouched (ragged row count, fast and fallback paths)."""
     from paper_1911_02079_amd import synth

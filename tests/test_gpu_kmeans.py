@@ -96,6 +96,25 @@ def test_dimensions_above_128(e4q, oracle_lib, dim, dtype):
     compare(e4q, oracle_lib, t, 7, f"chunked dim={dim}")
 
 
+def random_shapes(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        dim = int(rng.choice([rng.integers(1, 17), rng.integers(17, 129), rng.integers(129, 400), 8 * rng.integers(3, 17)]))
+        rows = min(int(10 ** rng.uniform(2.0, 4.8)), 3_000_000 // dim)
+        out.append((rows, dim, bool(rng.integers(0, 2)), int(rng.integers(0, 13))))
+    return out
+
+
+@pytest.mark.parametrize("rows,dim,half,iters", random_shapes(40, 19110207))
+def test_random_shapes(e4q, oracle_lib, rows, dim, half, iters):
+    """Seeded random (rows, dim, input type, rounds): whichever kernel the shape selects matches the oracle."""
+    from paper_1911_02079_amd import synth
+
+    t = synth.mixture_table(rows, dim, seed=7 * rows + dim, device="cuda")
+    compare(e4q, oracle_lib, t.half() if half else t, iters, f"random shape rows={rows} dim={dim}")
+
+
 @pytest.mark.parametrize("iters", [0, 1, 2, 7, 40])
 def test_round_counts(e4q, oracle_lib, iters):
     from paper_1911_02079_amd import synth

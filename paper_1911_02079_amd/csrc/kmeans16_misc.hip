@@ -122,9 +122,14 @@ __global__ void __launch_bounds__(64) kmeans16_chunk_kernel(KMeansArgs a, int32_
             for (int c0 = 0; c0 < d; c0 += kChunk) {
                 const int n = d - c0 < kChunk ? d - c0 : kChunk;
                 load_chunk(src + c0, n, vec, x);
+                if (n == kChunk) {  // whole chunk: no test per element, so the elements' chains interleave
 #pragma unroll
-                for (int e = 0; e < kChunk; ++e)
-                    if (e < n) lloyd_add(scratch, lane, nearest_centre_sorted(x[e], c), x[e]);  // scalar branch
+                    for (int e = 0; e < kChunk; ++e) lloyd_add(scratch, lane, nearest_centre_sorted(x[e], c), x[e]);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < kChunk; ++e)
+                        if (e < n) lloyd_add(scratch, lane, nearest_centre_sorted(x[e], c), x[e]);  // scalar branch
+                }
             }
         } else {
 #pragma unroll 1

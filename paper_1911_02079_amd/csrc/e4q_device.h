@@ -30,11 +30,14 @@ __device__ __forceinline__ float opaque(float v)
     return v;
 }
 
-__device__ __forceinline__ float through_f16(float v) { return opaque((float)(_Float16)v); }
+// Rounding to binary16 always starts from a finished binary32 value: the input is hidden as well, so that
+// the conversion cannot be merged with the operation that produced it into one mixed-precision
+// instruction with a single rounding (seen with a multiply-add as producer).
+__device__ __forceinline__ float through_f16(float v) { return opaque((float)(_Float16)opaque(v)); }
 
 __device__ __forceinline__ uint16_t f16_bits(float v)
 {
-    _Float16 h = (_Float16)v;
+    _Float16 h = (_Float16)opaque(v);
     return __builtin_bit_cast(uint16_t, h);
 }
 

@@ -96,6 +96,29 @@ def test_dimensions_above_128(e4q, oracle_lib, dim, dtype):
     compare(e4q, oracle_lib, t, 7, f"chunked dim={dim}")
 
 
+def test_outputs_do_not_overrun(e4q):
+    """Guard bands around indices and codebooks stay untouched (masked-tail rows staged through LDS, chunked
+    rows, plain rows; ragged row counts)."""
+    from paper_1911_02079_amd import synth
+
+    for dim, rows in ((64, 64 * 7 + 5), (50, 64 * 7 + 1), (101, 64 * 9 + 63), (23, 64 * 5 + 31), (200, 64 * 3 + 2),
+                      (130, 64 * 3 + 2), (13, 77)):
+        t = synth.mixture_table(rows, dim, seed=31 + dim, device="cuda")
+        nb = (dim + 1) // 2
+        say(f"guard bands dim={dim} rows={rows}")
+        ibuf = torch.full((rows * nb + 256,), 0xA5, dtype=torch.uint8, device="cuda")
+        cbuf = torch.full((rows * 16 + 128,), -3.0, dtype=torch.float16, device="cuda")
+        out = (ibuf[128:128 + rows * nb].reshape(rows, nb), cbuf[64:64 + rows * 16].reshape(rows, 16))
+        e4q.quantize_rowwise_kmeans16(t, 4, out=out)
+        torch.cuda.synchronize()
+        assert bool((ibuf[:128] == 0xA5).all()) and bool((ibuf[128 + rows * nb:] == 0xA5).all())
+        assert bool((cbuf[:64] == -3.0).all()) and bool((cbuf[64 + rows * 16:] == -3.0).all())
+        xbuf = torch.full((rows * dim + 64,), 7.0, device="cuda")
+        e4q.dequantize_codebook(*out, dim, out=xbuf[32:32 + rows * dim].reshape(rows, dim))
+        torch.cuda.synchronize()
+        assert bool((xbuf[:32] == 7.0).all()) and bool((xbuf[32 + rows * dim:] == 7.0).all())
+
+
 def random_shapes(n, seed):
     rng = np.random.default_rng(seed)
     out = []

@@ -423,10 +423,11 @@ def test_outputs_do_not_overrun(e4q):
     """Guard bands around the outputs stay untouched (ragged row count, fast and fallback paths)."""
     from paper_1911_02079_amd import synth
 
-    for dim, rows in ((64, 64 * 3 + 5), (13, 64 * 3 + 5), (64, 64 * 512 + 5), (200, 64 * 512 + 5)):
+    for dim, rows in ((64, 64 * 3 + 5), (13, 64 * 3 + 5), (64, 64 * 512 + 5), (200, 64 * 512 + 5), (13, 64 * 512 + 5),
+                      (100, 64 * 512 + 1), (127, 64 * 600 + 63), (33, 150_001), (1001, 64 * 512 + 5)):
         t = synth.gaussian_table(rows, dim, 0.1, seed=9, device="cuda")
         nb = (dim + 1) // 2
-        say(f"guard bands dim={dim}")
+        say(f"guard bands dim={dim} rows={rows}")
         cbuf = torch.full((rows * nb + 256,), 0xA5, dtype=torch.uint8, device="cuda")
         sbuf = torch.full((rows + 64,), -3.0, dtype=torch.float16, device="cuda")
         bbuf = torch.full((rows + 64,), -3.0, dtype=torch.float16, device="cuda")

@@ -128,9 +128,10 @@ def test_batch_grouping(e4q, oracle_lib):
 
 
 # --------------------------------------------------------------------------------------------
-# Every kernel layout.  The library picks by (rows, dim, ratio): one row per lane for many rows and
-# dim in 8, 16, ..., 128; otherwise L lanes per row with E elements per lane (E = 8 for few rows,
-# up to 128 for many rows), unmasked / masked per block of 8 / masked per element.
+# Every kernel layout.  The library picks by (rows, dim, ratio) with a cost model: one row per lane for
+# large tables of dimension up to 128 (a masked tail when the dimension is not a multiple of 8); otherwise
+# L lanes per row with E elements per lane (E = 8 for few rows, 16 to 64 for mid-sized tables, up to 128
+# above dimension 128), unmasked / masked per block of 8 / masked per element.
 # --------------------------------------------------------------------------------------------
 MANY = 64 * 512 + 17   # enough rows for the one-row-per-lane kernels (and a ragged tail)
 

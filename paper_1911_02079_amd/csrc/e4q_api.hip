@@ -373,6 +373,6 @@ const char* e4q_strerror(int code)
 
 const char* e4q_last_hip_error(void) { return g_hip_error; }
 
-int e4q_version(void) { return 100; }  // 0.1.0
+int e4q_version(void) { return 200; }  // 0.2.0
 
 }  // extern "C"

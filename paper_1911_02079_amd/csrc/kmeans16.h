@@ -49,6 +49,9 @@ __device__ __forceinline__ int nearest_centre(float x, const float (&c)[kK])
 // first nearest one, and a four-step bisection over that predicate finds their number: 4 compares and
 // 11 selects instead of 15 and 15.  The probe positions 7; 3|11; 1|5|9|13; 0|2|..|14 are picked by
 // selects on the earlier outcomes, because a register array cannot be indexed at run time.
+// UNIT scales the result (index * UNIT, UNIT a power of two), so that a caller that needs a byte offset
+// gets it from the selects themselves.
+template <int UNIT = 1>
 __device__ __forceinline__ int nearest_centre_sorted(float x, const float (&c)[kK])
 {
     float s[kK];
@@ -69,7 +72,7 @@ __device__ __forceinline__ int nearest_centre_sorted(float x, const float (&c)[k
     const float w0 = b2 ? v2 : v0, w1 = b2 ? v3 : v1;
     const float p0 = b1 ? w1 : w0;
     const bool b0 = p0 > m;
-    return (b3 ? 8 : 0) | (b2 ? 4 : 0) | (b1 ? 2 : 0) | (b0 ? 1 : 0);
+    return (b3 ? 8 * UNIT : 0) | (b2 ? 4 * UNIT : 0) | (b1 ? 2 * UNIT : 0) | (b0 ? UNIT : 0);
 }
 
 // True when every lane of the wave holds centres in non-decreasing order.  A grid is, and a Lloyd
@@ -119,6 +122,16 @@ __device__ __forceinline__ void lloyd_add(LloydScratch& s, int lane, int a, floa
     const int slot = a * 64 + lane;
     __hip_atomic_fetch_add(&s.sum[slot], (double)x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
     __hip_atomic_fetch_add(&s.cnt[slot].x, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+}
+
+// The same with the slot given as a byte offset: cluster * 512 | lane * 8 (sums and counts both have
+// 8-byte slots, so one offset serves both arrays).
+__device__ __forceinline__ void lloyd_add_at(LloydScratch& s, int byte_offset, float x)
+{
+    double* sum = reinterpret_cast<double*>(reinterpret_cast<char*>(s.sum) + byte_offset);
+    uint32_t* cnt = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(s.cnt) + byte_offset);
+    __hip_atomic_fetch_add(sum, (double)x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+    __hip_atomic_fetch_add(cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
 }
 
 // All 32 LDS reads are issued before the first division and the 16 divisions carry no branch, so
@@ -199,7 +212,7 @@ __device__ __forceinline__ void kmeans16_rpl_body(const KMeansArgs& a, int d, Ll
         if (!a.force_scan && wave_centres_sorted(c)) {
 #pragma unroll
             for (int e = 0; e < D; ++e)
-                if (!TAIL || e < D - 7 || e < d) lloyd_add(scratch, lane, nearest_centre_sorted(x[e], c), x[e]);
+                if (!TAIL || e < D - 7 || e < d) lloyd_add_at(scratch, nearest_centre_sorted<512>(x[e], c) | (lane * 8), x[e]);
         } else {
             // rolled, re-reading the row: x[] cannot be indexed by a loop counter
 #pragma unroll 1

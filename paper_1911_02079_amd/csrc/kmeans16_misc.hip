@@ -41,7 +41,7 @@ __global__ void __launch_bounds__(64) kmeans16_any_kernel(KMeansArgs a, int32_t 
         if (!a.force_scan && wave_centres_sorted(c)) {  // uniform over the wave's live lanes
             for (int e = 0; e < d; ++e) {
                 const float v = (float)src[e];
-                lloyd_add(scratch, lane, nearest_centre_sorted(v, c), v);
+                lloyd_add_at(scratch, nearest_centre_sorted<512>(v, c) | (lane * 8), v);
             }
         } else {
             for (int e = 0; e < d; ++e) {
@@ -124,11 +124,11 @@ __global__ void __launch_bounds__(64) kmeans16_chunk_kernel(KMeansArgs a, int32_
                 load_chunk(src + c0, n, vec, x);
                 if (n == kChunk) {  // whole chunk: no test per element, so the elements' chains interleave
 #pragma unroll
-                    for (int e = 0; e < kChunk; ++e) lloyd_add(scratch, lane, nearest_centre_sorted(x[e], c), x[e]);
+                    for (int e = 0; e < kChunk; ++e) lloyd_add_at(scratch, nearest_centre_sorted<512>(x[e], c) | (lane * 8), x[e]);
                 } else {
 #pragma unroll
                     for (int e = 0; e < kChunk; ++e)
-                        if (e < n) lloyd_add(scratch, lane, nearest_centre_sorted(x[e], c), x[e]);  // scalar branch
+                        if (e < n) lloyd_add_at(scratch, nearest_centre_sorted<512>(x[e], c) | (lane * 8), x[e]);  // scalar branch
                 }
             }
         } else {

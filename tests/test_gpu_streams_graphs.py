@@ -49,20 +49,26 @@ def test_two_streams_at_once(e4q, oracle_lib):
     assert np.array_equal(out_b[0].cpu().numpy()[rows], o[0]) and np.array_equal(f16_bits(out_b[1])[rows], o[1])
 
 
-def test_capture_into_a_graph_and_replay(e4q, oracle_lib):
+@pytest.mark.parametrize("rows,dim", [(70_003, 64), (40_001, 100)])
+def test_capture_into_a_graph_and_replay(e4q, oracle_lib, rows, dim):
+    """dim 64: the plain kernels; dim 100: the masked-tail kernels that stage rows through LDS."""
     from paper_1911_02079_amd import synth
 
-    rows, dim = 70_003, 64
     table = synth.outlier_table(rows, dim, seed=10, device="cuda")
     out = e4q.alloc_outputs(rows, dim, "cuda")
     xh = torch.empty((rows, dim), device="cuda")
     indices, offsets = synth.lookup_bags(rows, 5_000, 1, 20, device="cuda")
     pooled = torch.empty((5_000, dim), device="cuda")
+    kidx = torch.empty((rows, (dim + 1) // 2), dtype=torch.uint8, device="cuda")
+    kcb = torch.empty((rows, 16), dtype=torch.float16, device="cuda")
+    kxh = torch.empty((rows, dim), device="cuda")
 
     def path():
         e4q.quantize_rowwise_greedy(table, 200, 0.16, out=out)
         e4q.dequantize(*out, dim, out=xh)
         e4q.sparse_lengths_sum(*out, dim, indices, offsets, out=pooled)
+        e4q.quantize_rowwise_kmeans16(table, 5, out=(kidx, kcb))
+        e4q.dequantize_codebook(kidx, kcb, dim, out=kxh)
 
     path()  # eager reference
     torch.cuda.synchronize()
@@ -78,14 +84,15 @@ def test_capture_into_a_graph_and_replay(e4q, oracle_lib):
         table.copy_(new)
         path()
         torch.cuda.synchronize()
-        eager = (out[0].clone(), out[1].clone(), out[2].clone(), xh.clone(), pooled.clone())
-        for t in (*out, xh, pooled):
+        eager = (out[0].clone(), out[1].clone(), out[2].clone(), xh.clone(), pooled.clone(), kidx.clone(), kcb.clone(),
+                 kxh.clone())
+        for t in (*out, xh, pooled, kidx, kcb, kxh):
             t.zero_()
         torch.cuda.synchronize()
         say(f"replay {k}")
         graph.replay()
         torch.cuda.synchronize()
-        for got, want in zip((*out, xh, pooled), eager):
-            assert torch.equal(got, want), f"replay {k}"
+        for got, want in zip((*out, xh, pooled, kidx, kcb, kxh), eager):
+            assert torch.equal(got.view(torch.uint8), want.view(torch.uint8)), f"replay {k}"
     o = oracle_lib.quantize_rowwise_greedy(table[:2000].cpu().numpy(), 200, 0.16)
     assert np.array_equal(out[0][:2000].cpu().numpy(), o[0])

@@ -56,7 +56,7 @@ extern "C" {
 /*
  * Row-wise uniform n-bit quantization (n = 4 in the paper) with greedy search of the clipping range
  * (Algorithm 1; quantizer and stored parameters of Eq. 1; loss of Eq. 2; binary16 scale and
- * bias as in the "(FP16)" variants of Section 4).
+ * bias as in the "(FP16)" variants of Section 5).
  *
  * For each row X independently: start from [min X, max X], stepsize = (max - min)/n_bins;
  * n_iter = ceil(n_bins * ratio) times (at most n_bins - 1) score "lower bound up one step"
@@ -71,7 +71,7 @@ extern "C" {
  *
  *   table       [in]  rows x dim elements of `dtype`, `row_stride` elements between rows
  *   dtype             E4Q_F32 or E4Q_F16 (binary16 inputs are widened exactly)
- *   nbits             4 (the paper's subject); 8 (its ASYM-8BITS baseline, Section 4) and 2 are
+ *   nbits             4 (the paper's subject); 8 (its ASYM-8BITS baseline, Section 5) and 2 are
  *                     accepted too and differ only in the number of levels and the packing
  *   n_bins            b of Algorithm 1 (default in the paper: 200)
  *   ratio             r of Algorithm 1 (default in the paper: 0.16), 0 <= ratio < 1
@@ -123,7 +123,7 @@ int e4q_quantize_rowwise_greedy_batch(const e4q_table_desc* descs, int32_t n_tab
 
 /*
  * Row-wise codebook quantization ("KMEANS": Section 3, "Codebook-based Quantization"; initial
- * centres and binary16 codebooks as in Section 4).  For each row independently, 1-D k-means with
+ * centres and binary16 codebooks as in Section 5).  For each row independently, 1-D k-means with
  * 16 centres: centres start on the uniform grid min + k*(max-min)/15; `lloyd_iters` rounds of
  * (assign every value to its nearest centre -- |x - c| in binary32, the lowest index among equal
  * distances --, move every non-empty cluster's centre to the mean of its members -- summed in
@@ -177,8 +177,11 @@ int e4q_sparse_lengths_sum(const uint8_t* codes, const uint16_t* scale_f16, cons
 /*
  * Fused lookup records.  A lookup of one row needs its codes, its scale and its bias; kept in
  * three arrays they sit in three different places of HBM.  e4q_fuse_rows copies a quantized table
- * into one record per row, `row_pitch` bytes apart (as the lookup operator of Section 4 reads it):
+ * into one record per row, `row_pitch` bytes apart:
  *     [ codes: ceil(dim/2) bytes ][ pad to an even offset ][ scale f16 ][ bias f16 ][ pad: zeros ]
+ * This record layout is a choice of this library, not the paper's: Section 4 and Table 1 say what
+ * the lookup operator computes (4-bit rows are read and de-quantized while they are summed) and time
+ * it in sums per second, and describe no memory layout.
  * e4q_fused_row_bytes(dim) is the smallest record (dim/2 + 4 for even dim/2: the d/2 + 4 bytes per
  * row behind Table 3's sizes); row_pitch must be even and at least that (for example 128 to give
  * every record of a dim-128 table its own 128-byte line).  Host-only helper; negative on bad dim.

@@ -13,7 +13,7 @@
  *     x_float = scale * x_int + bias),
  *   - the loss f(xmin, xmax) = || X - Q(X, xmin, xmax) ||_2^2      (Eq. 2),
  *   - the greedy search over clipping ranges                  (Algorithm 1),
- *   - FP16 storage of the per-row scale and bias   (Section 4, "(FP16)" rows
+ *   - FP16 storage of the per-row scale and bias   (Section 5, "(FP16)" rows
  *     of Tables 2 and 3).
  *
  * The paper leaves the floating-point realisation open.  The readings taken

@@ -6,7 +6,7 @@
  * nothing with the HIP library.
  *
  * What it follows: Section 3, "Codebook-based Quantization" -- k-means clustering of each row
- * vector into a 16-value codebook, each value replaced by the index of its cluster; Section 4 --
+ * vector into a 16-value codebook, each value replaced by the index of its cluster; Section 5 --
  * cluster centres initialised from the uniform quantization grid of ASYM, codebooks stored in
  * binary16 ("(FP16)").  Bytes per row: d/2 of indices + 16 * 2 of codebook (Table 3, KMEANS row).
  *

@@ -53,7 +53,8 @@ int e4q_oracle_sparse_lengths_sum(const uint8_t *codes, const uint16_t *scale_f1
 /*
  * Fused row layout for lookups: one record per row, `row_pitch` bytes apart, holding the row's
  * packed codes followed (at the next even offset) by its binary16 scale and bias -- everything a
- * lookup of that row needs sits in one place, as in the operator of Section 4.
+ * lookup of that row needs sits in one place.  The layout is this build's own choice: Section 4 and
+ * Table 1 define what the lookup operator computes and time it, and describe no record layout.
  *   record = [ codes: ceil(dim/2) bytes ][ pad to even ][ scale: 2 bytes ][ bias: 2 bytes ][ pad ]
  * Padding bytes are written as 0.  Returns -1 if row_pitch is odd or too small.
  */

@@ -1,4 +1,4 @@
-// Row-wise 16-value codebook by 1-D k-means (Section 3, "Codebook-based Quantization"; Section 4:
+// Row-wise 16-value codebook by 1-D k-means (Section 3, "Codebook-based Quantization"; Section 5:
 // centres start on ASYM's uniform grid, codebooks are stored in binary16).
 //
 // One table row per lane, the row in registers (dimension a compile-time constant), the 16 centres

@@ -3,7 +3,7 @@
 This module only draws random inputs; it holds none of the quantization
 arithmetic and is the one piece of code that both the HIP path's tests and the
 CPU oracle's tests use.  The tables stand in for the trained recommendation
-tables of the paper's experiments (Section 4: up to 50 M rows, embedding
+tables of the paper's experiments (Section 5: up to 50 M rows, embedding
 dimension 8 to 128), which are not available here: same shapes, value
 distributions chosen to exercise the clipping search (Gaussian rows, rows with
 heavy-tailed outliers, Laplace rows with a per-row offset, a mixed batch of

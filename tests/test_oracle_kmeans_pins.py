@@ -186,3 +186,56 @@ def test_optimal_1d_clustering_is_a_lower_bound(oracle_lib):
         opt = best[16, n]
         assert got[r] >= opt * (1 - 1e-6) - 1e-12
         assert got[r] <= 50 * opt + 1e-6
+
+
+def test_binary16_tables_are_widened_exactly(oracle_lib):
+    """A binary16 table must give what the same values give as a binary32 table: widening is exact
+    (NumPy's own conversion feeds the binary32 side, which every other pin covers), so codebook,
+    indices and unrounded centres are equal bit for bit, for clustered rows and for dim <= 16.
+    Catches: a binary16 row read at the wrong stride or offset, bit patterns read as integers,
+    a widening that is not the IEEE one."""
+    from paper_1911_02079_amd import synth
+
+    for dim, seed in [(64, 31), (33, 32), (128, 33), (16, 34), (7, 35)]:
+        t16 = synth.mixture_table(60, dim, seed=seed).numpy().astype(np.float16)
+        # subnormals and both zeros belong to binary16 too
+        t16[0, 0], t16[1, 1 % dim], t16[2, 2 % dim] = np.float16(6e-8), np.float16(-0.0), np.float16(-3e-6)
+        got = oracle_lib.quantize_rowwise_kmeans16(t16, 20, return_centres=True)
+        want = oracle_lib.quantize_rowwise_kmeans16(t16.astype(np.float32), 20, return_centres=True)
+        for g, w in zip(got, want):
+            assert np.array_equal(g, w)
+        assert dim <= 16 or len(np.unique(got[0])) > 16  # the table is not degenerate
+
+
+def test_populated_grid_fixed_point_from_binary16(oracle_lib):
+    """The fixed-point pin again with the table handed over as binary16 (every grid value below is
+    exact in binary16): exact codebook, indices and reconstruction."""
+    rng = np.random.default_rng(5)
+    for lo, s, dim in [(-2.0, 0.25, 64), (0.5, 2.0 ** -6, 33), (-8.0, 1.0, 128)]:
+        k = np.concatenate([np.arange(16), rng.integers(0, 16, dim - 16)])
+        k = np.stack([rng.permutation(k) for _ in range(20)])
+        table = (lo + k * s).astype(np.float16)
+        assert np.all(table.astype(np.float64) == lo + k * s)
+        idx, cb = oracle_lib.quantize_rowwise_kmeans16(table, 20)
+        assert np.array_equal(oracle_lib.unpack_codes(idx, dim), k.astype(np.uint8))
+        assert np.all(f16_to_f64(cb) == lo + np.arange(16) * s)
+        assert np.array_equal(oracle_lib.dequantize_codebook(idx, cb, dim), table.astype(np.float32))
+
+
+@pytest.mark.parametrize("dim,m,rounds", [(24, 5, 2), (48, 7, 20)])
+def test_exact_rational_lloyd_from_binary16(oracle_lib, dim, m, rounds):
+    """Exact rational Lloyd rounds on small integer rows (exact in binary16) handed over as binary16."""
+    rng = np.random.default_rng(100 + dim)
+    used = 0
+    for _ in range(30):
+        x = rng.integers(0, 15 * m + 1, dim)
+        x[0], x[1] = 0, 15 * m
+        x = x - (15 * m) // 2
+        centres, _, tie = exact_lloyd.lloyd(x, rounds)
+        if tie:
+            continue
+        used += 1
+        _, _, c32 = oracle_lib.quantize_rowwise_kmeans16(x[None, :].astype(np.float16), rounds, return_centres=True)
+        want = np.array([float(c) for c in centres])
+        assert np.allclose(c32[0].astype(np.float64), want, rtol=2.0 ** -23, atol=0)
+    assert used >= 8

@@ -27,6 +27,11 @@ KMEANS_MUTANTS = {
                               "out[b] = (uint8_t)(q1 | (q0 << 4));\n            }\n        } else {"),
     "small_rows_clustered": ("if (dim <= K) {", "if (dim <= 0) {"),
     "squared_distance_sign": ("float dk = fabsf(x - c[k]);", "float dk = x - c[k];"),
+    "binary16_bits_read_as_integers": ("for (int k = 0; k < d; ++k) dst[k] = e4q_oracle_f16_to_f32(src[k]);",
+                                       "for (int k = 0; k < d; ++k) dst[k] = (float)src[k];"),
+    "binary16_rows_at_binary32_pitch": ("const uint16_t *src = (const uint16_t *)table + row * row_stride;",
+                                        "const uint16_t *src = (const uint16_t *)table + 2 * row * row_stride;"),
+    "binary16_row_starts_one_late": ("dst[k] = e4q_oracle_f16_to_f32(src[k]);", "dst[k] = e4q_oracle_f16_to_f32(src[k ? k : 1]);"),
 }
 
 SLS_MUTANTS = {
@@ -62,6 +67,10 @@ MUTANTS = {
     "bias_is_not_xmin": ("*bias_f16 = e4q_oracle_f32_to_f16(lo);", "*bias_f16 = e4q_oracle_f32_to_f16(hi);"),
     "error_not_squared": ("work[k] = e * e;", "work[k] = fabsf(e);"),
     "f16_ties_away": ("if (rem > 0x1000u || (rem == 0x1000u && (h & 1u)))", "if (rem >= 0x1000u)"),
+    "binary16_bits_read_as_integers": ("for (int k = 0; k < d; ++k) dst[k] = e4q_oracle_f16_to_f32(src[k]);",
+                                       "for (int k = 0; k < d; ++k) dst[k] = (float)src[k];"),
+    "binary16_rows_at_binary32_pitch": ("const uint16_t *src = (const uint16_t *)table + row * row_stride;",
+                                        "const uint16_t *src = (const uint16_t *)table + 2 * row * row_stride;"),
 }
 
 

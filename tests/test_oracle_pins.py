@@ -409,7 +409,31 @@ def test_numpy_twin_bit_identical(oracle_lib, dim, b, r, literal):
 
 
 # ----------------------------------------------------------------------------------------------
-# Other bit widths through the same code: n = 8 is the paper's ASYM-8BITS baseline (Section 4),
+# binary16 tables: widening is exact, so a binary16 table must give what the same values give as a
+# binary32 table (NumPy's conversion feeds the binary32 side, which the pins above cover).
+# Catches: binary16 rows read at the wrong pitch or offset, bit patterns read as integers.
+# ----------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dim", [8, 37, 64, 128])
+def test_binary16_tables_are_widened_exactly(oracle_lib, dim):
+    from paper_1911_02079_amd import synth
+
+    t16 = synth.outlier_table(40, dim, seed=70 + dim).numpy().astype(np.float16)
+    t16[0, 0], t16[1, 1], t16[2, 2] = np.float16(6e-8), np.float16(-0.0), np.float16(-3e-6)
+    got = oracle_lib.quantize_rowwise_greedy(t16, 200, 0.16, return_search=True)
+    want = oracle_lib.quantize_rowwise_greedy(t16.astype(np.float32), 200, 0.16, return_search=True)
+    for g, w in zip(got, want):
+        assert np.array_equal(g, w)
+    assert len(np.unique(got[0])) > 8
+    # and the exact-grid pin from a binary16 table: codes are the grid indices
+    k = np.concatenate([np.arange(16), np.random.default_rng(dim).integers(0, 16, max(dim - 16, 0))])[None, :]
+    grid = (-0.5 + k * 0.0625).astype(np.float16)
+    codes, sc, bi = oracle_lib.quantize_rowwise_greedy(grid, 200, 0.16)
+    assert np.array_equal(oracle_lib.unpack_codes(codes, k.shape[1])[:, : k.shape[1]], k.astype(np.uint8))
+    assert f16_bits_to_f64(sc)[0] == 0.0625 and f16_bits_to_f64(bi)[0] == -0.5
+
+
+# ----------------------------------------------------------------------------------------------
+# Other bit widths through the same code: n = 8 is the paper's ASYM-8BITS baseline (Section 5),
 # n = 2 the next power of two down.  2^n - 1 levels, 8/n codes per byte, lowest bits first.
 # ----------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("nbits", [2, 8])

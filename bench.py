@@ -113,7 +113,7 @@ def bench_sls(args, e4q, synth, torch, gen, rows, dim, params) -> int:
     indices, offsets = synth.lookup_bags(rows, n_bags, 1, params["max_len"], device="cuda:0")
     n_lookups = indices.numel()
     out = torch.empty((n_bags, dim), dtype=torch.float32, device="cuda:0")
-    pitch = e4q.fused_row_bytes(dim)
+    pitch = args.row_pitch or e4q.fused_row_bytes(dim)
     fused = e4q.fuse_rows(codes, scale, bias, dim, pitch)  # one-off re-layout of the table, not timed
     run = lambda: e4q.sparse_lengths_sum_fused(fused, dim, indices, offsets, out=out)  # noqa: E731
 
@@ -165,8 +165,9 @@ def bench_sls(args, e4q, synth, torch, gen, rows, dim, params) -> int:
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": args.workload, "rows": rows, "dim": dim, "n_bags": n_bags, "lookups": n_lookups,
                    "bag_lengths": f"uniform 1..{params['max_len']}", "index_dtype": "int64",
-                   "step": "sparse_lengths_sum_fused over all bags, fused records of 68 bytes resident in HBM "
-                           "(680 MB, not cache resident)"},
+                   "row_pitch": pitch, "nontemporal_gathers": bool(args.sls_nontemporal),
+                   "step": f"sparse_lengths_sum_fused over all bags, fused records {pitch} bytes apart resident in HBM "
+                           f"({rows * pitch / 1e6:.0f} MB, not cache resident)"},
         "kernels": {"sls_fused_w8_kernel": {"avg_ms": ms, "lookups_per_s": n_lookups / (ms * 1e-3),
                                             "G_sums_per_s": sums / (ms * 1e-3) / 1e9, "row_pitch": pitch},
                     "sls_fused_w8_kernel (row_pitch 128)": {"avg_ms": line_ms},
@@ -175,7 +176,8 @@ def bench_sls(args, e4q, synth, torch, gen, rows, dim, params) -> int:
         "roofline": {"kernel": "sls_fused_w8_kernel", "bound": "hbm", "achieved": alg_bytes / (ms * 1e-3) / 1e9,
                      "peak": PEAK_HBM_BYTES / 1e9, "unit": "GB/s", "frac": alg_bytes / (ms * 1e-3) / PEAK_HBM_BYTES,
                      "bytes_per_lookup": dim // 2 + 4 + indices.element_size(), "bytes_per_bag": 4 * dim + 8,
-                     "traffic": read_traffic(f"sls_fused_w8_kernel_{args.workload}_hbm_traffic.txt")},
+                     "traffic": read_traffic(f"sls_fused_w8_kernel_{args.workload}_hbm_traffic.txt")
+                     if not (args.row_pitch or args.sls_nontemporal) else None},
     }
     if not args.no_cpu_baseline:
         import oracle
@@ -259,6 +261,12 @@ def main() -> int:
     ap.add_argument("--ratio", type=float, default=-1.0, help="override r of Algorithm 1 (0 = plain min/max)")
     ap.add_argument("--half", action="store_true", help="feed the table as binary16")
     ap.add_argument("--nbits", type=int, default=4, choices=[2, 4, 8], help="code width of the uniform quantizer")
+    ap.add_argument("--layout", default="auto",
+                    help="thread layout of the greedy search: auto (the library's cost model), rpl (one row per "
+                         "lane) or E,L (L lanes per row, E elements each), through the greedy_layout diagnostic option")
+    ap.add_argument("--row-pitch", type=int, default=0,
+                    help="lookup workload: bytes between fused records (default: the smallest record, d/2 + 4)")
+    ap.add_argument("--sls-nontemporal", action="store_true", help="lookup workload: non-temporal record gathers")
     ap.add_argument("--no-cpu-baseline", action="store_true", help="skip the oracle timing (profiling runs)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device-to-device copy kernel three times, so that a "
@@ -279,6 +287,8 @@ def main() -> int:
         return 2
     e4q.binding.load_library()
     torch.cuda.set_device(0)
+    e4q.set_option("greedy_layout", e4q.greedy_layout_value(args.layout))
+    e4q.set_option("sls_nontemporal", 1 if args.sls_nontemporal else 0)
     method, gen, rows, dim, params = WORKLOADS[args.workload]
     if method == "sls":
         return bench_sls(args, e4q, synth, torch, gen, rows, dim, params)
@@ -302,12 +312,16 @@ def main() -> int:
         out = e4q.alloc_outputs(rows, dim, table.device, nbits)
         quantize = lambda: e4q.quantize_rowwise_greedy(table, n_bins, ratio, nbits=nbits, out=out)  # noqa: E731
         dequantize = lambda: e4q.dequantize(out[0], out[1], out[2], dim, nbits=nbits, out=xh)  # noqa: E731
-        # the library takes one row per lane when there are enough rows and dim is 8, 16, ..., 128
-        rpl = n_iter > 0 and (rows + 63) // 64 >= 512 and dim % 8 == 0 and dim <= 128
+        quantize()  # the library reports which thread layout it ran with
+        torch.cuda.synchronize()
+        chosen = e4q.get_option("greedy_layout_chosen")
+        rpl = chosen == 1
+        layout = "one row per lane" if rpl else f"E={chosen >> 8} elements x L={chosen & 0xff} lanes per row"
         q_name, dq_name = ("greedy_rpl_kernel" if rpl else "greedy_swl_kernel"), "dequantize_w4_kernel"
         ops_per_row = greedy_lane_ops_per_row(dim, n_iter)
         out_bytes_per_row = e4q.packed_bytes(dim, nbits) + 4
         config = {"n_bins": n_bins, "ratio": ratio, "candidate_ranges_per_row": 1 + 2 * n_iter, "nbits": nbits,
+                  "layout": layout, "layout_forced": args.layout != "auto",
                   "step": "quantize_rowwise_greedy + dequantize, table resident in HBM"}
         metric = f"rows quantized/sec (greedy {nbits}-bit)"
 
@@ -397,7 +411,8 @@ def main() -> int:
             "hbm_achieved_GBps": q_bytes / (q_ms * 1e-3) / 1e9,
             "hbm_frac": q_bytes / (q_ms * 1e-3) / PEAK_HBM_BYTES,
             "traffic": read_traffic(f"{q_name}_{args.workload}_hbm_traffic.txt")
-            if not (args.rows or args.dim or args.n_bins or args.ratio >= 0 or args.half or args.nbits != 4) else None,
+            if not (args.rows or args.dim or args.n_bins or args.ratio >= 0 or args.half or args.nbits != 4
+                    or args.layout != "auto") else None,
         },
     }
     if method == "greedy" and n_iter == 0:  # plain min/max: one pass over the data, bound by HBM

@@ -43,13 +43,14 @@ extern "C" {
 #define E4Q_ERR_BAD_DTYPE (-5)      /* dtype is neither E4Q_F32 nor E4Q_F16; index_bytes is neither 4 nor 8 */
 #define E4Q_ERR_LAUNCH (-6)         /* HIP reported an error when the kernel was enqueued */
 #define E4Q_ERR_BAD_ALIGNMENT (-7)  /* table pointer not aligned to its element size */
+#define E4Q_ERR_BAD_OPTION (-8)     /* unknown diagnostic option or value; a forced layout that cannot hold the call's dim */
 
 /* Element type of an input table. */
 #define E4Q_F32 0
 #define E4Q_F16 1
 
-/* Largest supported embedding dimension, row count and bag count (a launch has at most 2^31 - 1
- * workgroups and the smallest ones take four rows). */
+/* Largest supported embedding dimension, row count and bag count.  (A grid dimension holds fewer
+ * than 2^32 work-items; launches that need more are folded into two dimensions inside the library.) */
 #define E4Q_MAX_DIM 4096
 #define E4Q_MAX_ROWS 2147483648LL
 
@@ -138,10 +139,8 @@ int e4q_quantize_rowwise_greedy_batch(const e4q_table_desc* descs, int32_t n_tab
  *   centroids_f16  [out] rows x 16 binary16 values (32 bytes per row, dense)
  * Bytes per row: dim/2 + 32 (the KMEANS (FP16) sizes of Table 3).
  *
- * Diagnostic switch: with E4Q_KMEANS_FORCE_SCAN=1 in the environment (read at every call) the
- * kernels find the nearest centre by scanning all 16 instead of bisecting the ordered centres; the
- * outputs are the same bit for bit, only slower.  It exists so that the scan, which otherwise runs
- * only for rows whose centres fall out of order, can be exercised.
+ * (Diagnostic option "kmeans_force_scan", see e4q_set_option: the kernels then find the nearest
+ * centre by scanning all 16 instead of bisecting the ordered centres; same outputs bit for bit.)
  */
 int e4q_quantize_rowwise_kmeans16(const void* table, int dtype, int64_t rows, int32_t dim,
                                   int64_t row_stride, int32_t lloyd_iters, uint8_t* idx,
@@ -208,6 +207,33 @@ int e4q_sparse_lengths_sum_fused(const uint8_t* fused, int64_t rows, int32_t dim
  * error code for invalid arguments.
  */
 int32_t e4q_greedy_iterations(int32_t n_bins, float ratio);
+
+/*
+ * Diagnostic options, for tests, benchmarks and profiling (no passage of the paper: they change how
+ * a result is computed, never the result).  Process-wide, initially 0, read once per call by the
+ * entry points they concern; setting one while another thread is inside such a call affects that
+ * call or the next.  Host-only.
+ *
+ *   "greedy_layout"      0: the library picks the thread layout of the greedy search (default).
+ *                        1: one table row per lane (dim <= 128 only).
+ *                        (E << 8) | L: L lanes per row with E contiguous elements each,
+ *                        E in {8, 16, 32, 64, 128}, L a power of two <= 64 (<= 32 for E = 128).
+ *                        A forced layout needs E * L >= dim; the quantize calls return
+ *                        E4Q_ERR_BAD_OPTION otherwise.  The batch call then launches table by table.
+ *   "kmeans_force_scan"  1: e4q_quantize_rowwise_kmeans16 scans all 16 centres for every value
+ *                        instead of bisecting (the path otherwise taken only by rows whose centres
+ *                        fall out of order).
+ *   "sls_nontemporal"    1: e4q_sparse_lengths_sum_fused gathers records with non-temporal loads.
+ *   "greedy_layout_chosen"  read-only (e4q_get_option): the layout the last table handed to a
+ *                        single-table greedy launch ran with, in the encoding of "greedy_layout"
+ *                        (0 before the first such launch); grouped batch launches, which are
+ *                        always one row per lane, do not change it.
+ *
+ * e4q_set_option returns E4Q_OK, or E4Q_ERR_BAD_OPTION for an unknown name or a value the option
+ * does not take (nothing changes then).  e4q_get_option returns the value, or E4Q_ERR_BAD_OPTION.
+ */
+int e4q_set_option(const char* name, int64_t value);
+int64_t e4q_get_option(const char* name);
 
 /* Static, human-readable text for a return code (never NULL). */
 const char* e4q_strerror(int code);

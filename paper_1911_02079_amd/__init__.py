@@ -9,7 +9,7 @@ from . import synth  # noqa: F401
 
 __all__ = ["synth", "binding", "quantize_rowwise_greedy", "quantize_rowwise_greedy_batch", "dequantize",
            "greedy_iterations", "quantize_rowwise_kmeans16", "dequantize_codebook", "sparse_lengths_sum",
-           "fuse_rows", "sparse_lengths_sum_fused", "fused_row_bytes"]
+           "fuse_rows", "sparse_lengths_sum_fused", "fused_row_bytes", "set_option", "get_option"]
 
 
 def __getattr__(name):
@@ -19,7 +19,8 @@ def __getattr__(name):
         return importlib.import_module(".binding", __name__)
     if name in ("quantize_rowwise_greedy", "quantize_rowwise_greedy_batch", "dequantize", "greedy_iterations",
                 "alloc_outputs", "packed_bytes", "load_library", "E4QError", "quantize_rowwise_kmeans16", "dequantize_codebook",
-                "sparse_lengths_sum", "fuse_rows", "sparse_lengths_sum_fused", "fused_row_bytes"):
+                "sparse_lengths_sum", "fuse_rows", "sparse_lengths_sum_fused", "fused_row_bytes", "set_option", "get_option",
+                "greedy_layout_value"):
         import importlib
 
         return getattr(importlib.import_module(".binding", __name__), name)

@@ -73,6 +73,10 @@ def load_library() -> ctypes.CDLL:
     lib.e4q_sparse_lengths_sum_fused.restype = c.c_int
     lib.e4q_greedy_iterations.argtypes = [c.c_int32, c.c_float]
     lib.e4q_greedy_iterations.restype = c.c_int32
+    lib.e4q_set_option.argtypes = [c.c_char_p, c.c_int64]
+    lib.e4q_set_option.restype = c.c_int
+    lib.e4q_get_option.argtypes = [c.c_char_p]
+    lib.e4q_get_option.restype = c.c_int64
     lib.e4q_strerror.argtypes = [c.c_int]
     lib.e4q_strerror.restype = c.c_char_p
     lib.e4q_last_hip_error.argtypes = []
@@ -126,6 +130,30 @@ def greedy_iterations(n_bins: int, ratio: float) -> int:
     return n
 
 
+def set_option(name: str, value: int) -> None:
+    """e4q_set_option: a process-wide diagnostic switch ("greedy_layout", "kmeans_force_scan",
+    "sls_nontemporal"); see include/e4q.h."""
+    _check(int(load_library().e4q_set_option(name.encode(), int(value))))
+
+
+def get_option(name: str) -> int:
+    v = int(load_library().e4q_get_option(name.encode()))
+    if v < 0:
+        _check(v)
+    return v
+
+
+def greedy_layout_value(layout) -> int:
+    """Value of the "greedy_layout" option: None or "auto" -> 0, "rpl" -> 1 (one row per lane),
+    (E, L) or "E,L" -> (E << 8) | L."""
+    if layout is None or layout == "auto":
+        return 0
+    if layout == "rpl":
+        return 1
+    e, l = (int(v) for v in layout.split(",")) if isinstance(layout, str) else layout
+    return (int(e) << 8) | int(l)
+
+
 def packed_bytes(dim: int, nbits: int = 4) -> int:
     """Bytes of one row of codes: 8/nbits codes per byte."""
     per = 8 // nbits
@@ -141,6 +169,28 @@ def alloc_outputs(rows: int, dim: int, device, nbits: int = 4) -> Tuple[torch.Te
     return codes, scale, bias
 
 
+def _check_out(t: torch.Tensor, dtype: torch.dtype, shape: Tuple[int, ...], device, what: str) -> None:
+    """A caller-supplied output buffer must be exactly what the kernels write: dense, of the right
+    type and shape, on the table's device (a wrong one would be an out-of-bounds device write)."""
+    if not isinstance(t, torch.Tensor) or not t.is_cuda or t.device != device:
+        raise ValueError(f"{what} must be a GPU tensor on the input's device ({device})")
+    if t.dtype != dtype:
+        raise TypeError(f"{what} must be {dtype}, got {t.dtype}")
+    if tuple(t.shape) != tuple(shape) or not t.is_contiguous():
+        raise ValueError(f"{what} must be a dense tensor of shape {tuple(shape)}, got {tuple(t.shape)} "
+                         f"with strides {tuple(t.stride())}")
+
+
+def _check_greedy_out(out, rows: int, dim: int, nbits: int, device) -> None:
+    if nbits not in (2, 4, 8):
+        raise E4QError(-3, strerror(-3))
+    if len(out) != 3:
+        raise ValueError("out must be (codes, scale_f16, bias_f16)")
+    _check_out(out[0], torch.uint8, (rows, packed_bytes(dim, nbits)), device, "out codes")
+    _check_out(out[1], torch.float16, (rows,), device, "out scale")
+    _check_out(out[2], torch.float16, (rows,), device, "out bias")
+
+
 def quantize_rowwise_greedy(table: torch.Tensor, n_bins: int = 200, ratio: float = 0.16, nbits: int = 4,
                             out: Optional[Tuple[torch.Tensor, torch.Tensor, torch.Tensor]] = None,
                             stream: Optional[torch.cuda.Stream] = None):
@@ -149,6 +199,8 @@ def quantize_rowwise_greedy(table: torch.Tensor, n_bins: int = 200, ratio: float
     lib = load_library()
     _check_table(table)
     rows, dim = table.shape
+    if out is not None:
+        _check_greedy_out(out, rows, dim, nbits, table.device)
     codes, scale, bias = out if out is not None else alloc_outputs(rows, dim, table.device, nbits)
     with torch.cuda.device(table.device):
         rc = lib.e4q_quantize_rowwise_greedy(table.data_ptr(), _dtype_code(table), rows, dim,
@@ -169,6 +221,14 @@ def quantize_rowwise_greedy_batch(tables: Sequence[torch.Tensor], n_bins: int = 
     for t in tables:
         _check_table(t)
     device = tables[0].device
+    for t in tables:
+        if t.device != device:
+            raise ValueError("all tables of a batch must be on one device")
+    if out is not None:
+        if len(out) != len(tables):
+            raise ValueError("out must hold one (codes, scale_f16, bias_f16) per table")
+        for t, o in zip(tables, out):
+            _check_greedy_out(o, t.shape[0], t.shape[1], nbits, device)
     outs = out if out is not None else [alloc_outputs(t.shape[0], t.shape[1], device, nbits) for t in tables]
     descs = (TableDesc * len(tables))()
     for d, t, (codes, scale, bias) in zip(descs, tables, outs):
@@ -218,6 +278,11 @@ def quantize_rowwise_kmeans16(table: torch.Tensor, lloyd_iters: int = 20,
     if out is None:
         out = (torch.empty((rows, (dim + 1) // 2), dtype=torch.uint8, device=table.device),
                torch.empty((rows, 16), dtype=torch.float16, device=table.device))
+    else:
+        if len(out) != 2:
+            raise ValueError("out must be (idx, centroids_f16)")
+        _check_out(out[0], torch.uint8, (rows, (dim + 1) // 2), table.device, "out idx")
+        _check_out(out[1], torch.float16, (rows, 16), table.device, "out centroids")
     idx, cent = out
     with torch.cuda.device(table.device):
         rc = lib.e4q_quantize_rowwise_kmeans16(table.data_ptr(), _dtype_code(table), rows, dim,

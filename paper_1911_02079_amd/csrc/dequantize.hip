@@ -2,6 +2,7 @@
 //
 // Bound by HBM: d/2 + 4 bytes in, 4d bytes out per row.
 #include "e4q_device.h"
+#include "e4q_index.h"
 #include "e4q_launch.h"
 
 namespace e4q {
@@ -22,9 +23,9 @@ __global__ void __launch_bounds__(kDqBlock) dequantize_w4_kernel(const void* __r
     // One group of four elements per thread and no loop: neighbouring workgroups write neighbouring
     // memory (measured 20 % faster than a capped grid with a grid-stride loop).  WIDE selects
     // 64-bit index arithmetic for tables with 2^32 or more groups.
-    const int64_t w = (int64_t)blockIdx.x * kDqBlock + threadIdx.x;
+    const int64_t w = linear_block() * kDqBlock + threadIdx.x;
     if (w >= n_quads) return;
-    const int64_t row = WIDE ? w / quads_per_row : (int64_t)((uint32_t)w / quads_per_row);
+    const int64_t row = group_of<WIDE>(w, quads_per_row);
     const float scale = f16_bits_to_float(scale_f16[row]);
     const float bias = f16_bits_to_float(bias_f16[row]);
     uint32_t c;  // the four codes of this thread, NBITS each, first element lowest
@@ -50,8 +51,8 @@ __global__ void __launch_bounds__(kDqBlock) dequantize_any_kernel(const uint8_t*
     const uint32_t per = 8 / nbits;
     const uint32_t nbytes = (dim + per - 1) / per;
     const uint32_t mask = (1u << nbits) - 1u;
-    const int64_t stride = (int64_t)gridDim.x * kDqBlock;
-    for (int64_t e = (int64_t)blockIdx.x * kDqBlock + threadIdx.x; e < n_elems; e += stride) {
+    const int64_t stride = (int64_t)gridDim.x * gridDim.y * kDqBlock;
+    for (int64_t e = linear_block() * kDqBlock + threadIdx.x; e < n_elems; e += stride) {
         const int64_t row = e / dim;
         const uint32_t k = (uint32_t)(e - row * dim);
         const uint32_t byte = codes[row * nbytes + k / per];
@@ -70,13 +71,13 @@ __global__ void __launch_bounds__(kDqBlock) dequantize_flat4_kernel(const uint8_
                                                                    int64_t n_elems, uint32_t dim, uint32_t nbits,
                                                                    float* __restrict__ out)
 {
-    const int64_t e0 = ((int64_t)blockIdx.x * kDqBlock + threadIdx.x) * 4;
+    const int64_t e0 = (linear_block() * kDqBlock + threadIdx.x) * 4;
     if (e0 >= n_elems) return;
     const uint32_t per = 8 / nbits;
     const uint32_t nbytes = (dim + per - 1) / per;
     const uint32_t mask = (1u << nbits) - 1u;
-    int64_t row = WIDE ? e0 / dim : (int64_t)((uint32_t)e0 / dim);
-    uint32_t k = (uint32_t)(e0 - row * dim);
+    int64_t row = group_of<WIDE>(e0, dim);
+    uint32_t k = offset_in_group(e0, row, dim);
     float v[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -103,8 +104,8 @@ template <int NBITS>
 static void launch_w4(const void* codes, const uint16_t* scale_f16, const uint16_t* bias_f16, int64_t n_quads,
                       uint32_t quads_per_row, floatx4* out, hipStream_t stream)
 {
-    const dim3 grid((unsigned)((n_quads + kDqBlock - 1) / kDqBlock)), block(kDqBlock);
-    if (n_quads > 0xffffffffLL)
+    const dim3 grid = grid_for(blocks_for(n_quads, kDqBlock)), block(kDqBlock);
+    if (needs_wide_index(n_quads))
         hipLaunchKernelGGL((dequantize_w4_kernel<NBITS, true>), grid, block, 0, stream, codes, scale_f16, bias_f16,
                            n_quads, quads_per_row, out);
     else
@@ -119,7 +120,7 @@ hipError_t launch_dequantize(const uint8_t* codes, const uint16_t* scale_f16, co
     const int64_t n_quads = rows * (dim / 4);
     const bool fast = dim % 4 == 0 && (reinterpret_cast<uintptr_t>(codes) % group_bytes == 0) &&
                       (reinterpret_cast<uintptr_t>(out) % 16 == 0) &&
-                      (n_quads + kDqBlock - 1) / kDqBlock <= 0x7fffffffLL;
+                      blocks_for(n_quads, kDqBlock) >= 0;
     if (fast) {
         floatx4* o4 = reinterpret_cast<floatx4*>(out);
         const uint32_t qpr = (uint32_t)(dim / 4);
@@ -128,18 +129,18 @@ hipError_t launch_dequantize(const uint8_t* codes, const uint16_t* scale_f16, co
         else launch_w4<2>(codes, scale_f16, bias_f16, n_quads, qpr, o4, stream);
     } else {
         const int64_t n_elems = rows * dim;
-        const int64_t blocks4 = ((n_elems + 3) / 4 + kDqBlock - 1) / kDqBlock;
-        if (reinterpret_cast<uintptr_t>(out) % 16 == 0 && blocks4 <= 0x7fffffffLL) {
-            if (n_elems > 0xffffffffLL)
-                hipLaunchKernelGGL(dequantize_flat4_kernel<true>, dim3((unsigned)blocks4), dim3(kDqBlock), 0, stream,
+        const int64_t blocks4 = blocks_for((n_elems + 3) / 4, kDqBlock);
+        if (reinterpret_cast<uintptr_t>(out) % 16 == 0 && blocks4 >= 0) {
+            if (needs_wide_index(n_elems))
+                hipLaunchKernelGGL(dequantize_flat4_kernel<true>, grid_for(blocks4), dim3(kDqBlock), 0, stream,
                                    codes, scale_f16, bias_f16, n_elems, (uint32_t)dim, (uint32_t)nbits, out);
             else
-                hipLaunchKernelGGL(dequantize_flat4_kernel<false>, dim3((unsigned)blocks4), dim3(kDqBlock), 0, stream,
+                hipLaunchKernelGGL(dequantize_flat4_kernel<false>, grid_for(blocks4), dim3(kDqBlock), 0, stream,
                                    codes, scale_f16, bias_f16, n_elems, (uint32_t)dim, (uint32_t)nbits, out);
         } else {
             int64_t blocks = (n_elems + kDqBlock - 1) / kDqBlock;
-            if (blocks > 0x7fffffffLL) blocks = 0x7fffffffLL;  // the kernel loops over what is left
-            hipLaunchKernelGGL(dequantize_any_kernel, dim3((unsigned)blocks), dim3(kDqBlock), 0, stream, codes,
+            if (blocks > kMaxGridX) blocks = kMaxGridX;  // the kernel loops over what is left
+            hipLaunchKernelGGL(dequantize_any_kernel, grid_for(blocks), dim3(kDqBlock), 0, stream, codes,
                                scale_f16, bias_f16, n_elems, (uint32_t)dim, (uint32_t)nbits, out);
         }
     }

@@ -3,6 +3,7 @@
 #include "../../include/e4q.h"
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
@@ -19,6 +20,31 @@ int fail_launch(hipError_t err)
 {
     std::snprintf(g_hip_error, sizeof(g_hip_error), "%s: %s", hipGetErrorName(err), hipGetErrorString(err));
     return E4Q_ERR_LAUNCH;
+}
+
+// Diagnostic options (e4q_set_option): process-wide, read once per call.
+std::atomic<int64_t> g_greedy_layout{0};      // 0 automatic, 1 one row per lane, (E << 8) | L sub-wave layout
+std::atomic<int64_t> g_kmeans_force_scan{0};  // 1: scan all 16 centres instead of bisecting
+std::atomic<int64_t> g_sls_nontemporal{0};    // 1: gather records with non-temporal loads
+std::atomic<int64_t> g_greedy_layout_chosen{0};  // read-only: layout of the last single-table greedy launch
+
+std::atomic<int64_t>* find_option(const char* name)
+{
+    if (!name) return nullptr;
+    if (std::strcmp(name, "greedy_layout") == 0) return &g_greedy_layout;
+    if (std::strcmp(name, "kmeans_force_scan") == 0) return &g_kmeans_force_scan;
+    if (std::strcmp(name, "sls_nontemporal") == 0) return &g_sls_nontemporal;
+    if (std::strcmp(name, "greedy_layout_chosen") == 0) return &g_greedy_layout_chosen;
+    return nullptr;
+}
+
+bool layout_value_ok(int64_t v)
+{
+    if (v == 0 || v == 1) return true;
+    const int64_t e = v >> 8, l = v & 0xff;
+    if (e != 8 && e != 16 && e != 32 && e != 64 && e != 128) return false;
+    if (l < 1 || l > (e == 128 ? 32 : 64) || (l & (l - 1)) != 0) return false;
+    return true;
 }
 
 inline bool aligned(const void* p, size_t a) { return reinterpret_cast<uintptr_t>(p) % a == 0; }
@@ -42,6 +68,15 @@ int validate_table(const void* table, int dtype, int64_t rows, int32_t dim, int6
     if (!aligned(table, dtype == E4Q_F32 ? 4 : 2) || !aligned(scale_f16, 2) || !aligned(bias_f16, 2))
         return E4Q_ERR_BAD_ALIGNMENT;
     return E4Q_OK;
+}
+
+// A layout forced through the "greedy_layout" option must be able to hold a row of `dim` elements.
+int validate_forced_layout(int32_t dim)
+{
+    const int64_t forced = g_greedy_layout.load(std::memory_order_relaxed);
+    if (forced == 0) return E4Q_OK;
+    if (forced == 1) return (e4q::rpl_supports_dim(dim) || e4q::rpl_tail_supports_dim(dim)) ? E4Q_OK : E4Q_ERR_BAD_OPTION;
+    return (forced >> 8) * (forced & 0xff) >= dim ? E4Q_OK : E4Q_ERR_BAD_OPTION;
 }
 
 // Estimated duration of the greedy search, in SIMD cycles, for `rows` rows with `elems` elements per
@@ -91,7 +126,14 @@ int enqueue_greedy(const void* table, int dtype, int64_t rows, int32_t dim, int6
     // see layout_cost.  ratio == 0 is bound by HBM and always takes E = 8 (a wave then reads and
     // writes contiguous memory).
     int E = 0, L = 1;  // E == 0: one row per lane
-    if (n_iter == 0) {
+    const int64_t forced = g_greedy_layout.load(std::memory_order_relaxed);
+    if (forced == 1) {
+        if (!(e4q::rpl_supports_dim(dim) || e4q::rpl_tail_supports_dim(dim))) return E4Q_ERR_BAD_OPTION;
+    } else if (forced != 0) {
+        E = (int)(forced >> 8);
+        L = (int)(forced & 0xff);
+        if ((int64_t)E * L < dim) return E4Q_ERR_BAD_OPTION;
+    } else if (n_iter == 0) {
         E = dim <= 512 ? 8 : dim <= 1024 ? 16 : dim <= 2048 ? 32 : 64;
     } else {
         const bool rpl = e4q::rpl_supports_dim(dim) || e4q::rpl_tail_supports_dim(dim);
@@ -113,6 +155,9 @@ int enqueue_greedy(const void* table, int dtype, int64_t rows, int32_t dim, int6
             }
         }
     }
+    if (E != 0)
+        while (E * L < dim) L *= 2;
+    g_greedy_layout_chosen.store(E == 0 ? 1 : ((int64_t)E << 8) | L, std::memory_order_relaxed);
     hipError_t err;
     if (E == 0 && dim % 8 == 0) {
         err = dtype == E4Q_F32 ? e4q::launch_greedy_rpl_f32(a, dim, stream)
@@ -121,7 +166,6 @@ int enqueue_greedy(const void* table, int dtype, int64_t rows, int32_t dim, int6
         err = dtype == E4Q_F32 ? e4q::launch_greedy_rpl_tail_f32(a, dim, stream)
                                : e4q::launch_greedy_rpl_tail_f16(a, dim, stream);
     } else {
-        while (E * L < dim) L *= 2;
         if (E == 128)
             err = dtype == E4Q_F32 ? e4q::launch_greedy_swl_f32_big(a, dim, E, L, stream)
                                    : e4q::launch_greedy_swl_f16_big(a, dim, E, L, stream);
@@ -158,6 +202,8 @@ int e4q_quantize_rowwise_greedy(const void* table, int dtype, int64_t rows, int3
     if (rc != E4Q_OK) return rc;
     rc = validate_table(table, dtype, rows, dim, row_stride, codes, scale_f16, bias_f16);
     if (rc != E4Q_OK) return rc;
+    rc = validate_forced_layout(dim);
+    if (rc != E4Q_OK) return rc;
     return enqueue_greedy(table, dtype, rows, dim, row_stride, nbits, n_bins, e4q_greedy_iterations(n_bins, ratio),
                           codes, scale_f16, bias_f16, static_cast<hipStream_t>(hip_stream));
 }
@@ -174,6 +220,8 @@ int e4q_quantize_rowwise_greedy_batch(const e4q_table_desc* descs, int32_t n_tab
         const e4q_table_desc& d = descs[t];
         rc = validate_table(d.table, d.dtype, d.rows, d.dim, d.row_stride, d.codes, d.scale_f16, d.bias_f16);
         if (rc != E4Q_OK) return rc;
+        rc = validate_forced_layout(d.dim);
+        if (rc != E4Q_OK) return rc;
     }
     const int32_t n_iter = e4q_greedy_iterations(n_bins, ratio);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
@@ -181,7 +229,7 @@ int e4q_quantize_rowwise_greedy_batch(const e4q_table_desc* descs, int32_t n_tab
     std::vector<char> done((size_t)n_tables, 0);
     // Tables that share a dimension and an input type, and together have enough rows for the
     // one-row-per-lane kernels, go out in grouped launches of up to kMaxGroupTables tables.
-    if (n_iter > 0) {
+    if (n_iter > 0 && g_greedy_layout.load(std::memory_order_relaxed) == 0) {
         for (int32_t t = 0; t < n_tables; ++t) {
             if (done[t] || descs[t].rows == 0 || !e4q::rpl_supports_dim(descs[t].dim)) continue;
             std::vector<int32_t> members;
@@ -191,7 +239,7 @@ int e4q_quantize_rowwise_greedy_batch(const e4q_table_desc* descs, int32_t n_tab
                     members.push_back(u);
                     waves += (descs[u].rows + 63) / 64;
                 }
-            if (members.size() < 2 || waves < 512 || waves > 0x7fffffffLL) continue;
+            if (members.size() < 2 || waves < 512 || waves > 0x3ffffffLL) continue;  // 64 work-items each: below 2^32 per launch
             for (size_t first = 0; first < members.size(); first += e4q::kMaxGroupTables) {
                 e4q::GreedyGroup g;
                 g.n_tables = (int32_t)std::min<size_t>(e4q::kMaxGroupTables, members.size() - first);
@@ -273,8 +321,7 @@ int e4q_quantize_rowwise_kmeans16(const void* table, int dtype, int64_t rows, in
     a.centroids_f16 = centroids_f16;
     a.vec_loads = (aligned(table, 16) && (row_stride * esz) % 16 == 0) ? 1u : 0u;
     a.vec_stores = aligned(idx, 16) ? 2u : (aligned(idx, 4) ? 1u : 0u);
-    const char* scan = std::getenv("E4Q_KMEANS_FORCE_SCAN");
-    a.force_scan = (scan && scan[0] == '1') ? 1u : 0u;
+    a.force_scan = g_kmeans_force_scan.load(std::memory_order_relaxed) != 0 ? 1u : 0u;
     const hipError_t err = e4q::launch_kmeans16(a, dtype, dim, static_cast<hipStream_t>(hip_stream));
     return err == hipSuccess ? E4Q_OK : fail_launch(err);
 }
@@ -352,8 +399,24 @@ int e4q_sparse_lengths_sum_fused(const uint8_t* fused, int64_t rows, int32_t dim
         return E4Q_ERR_BAD_ALIGNMENT;
     const hipError_t err = e4q::launch_sparse_lengths_sum_fused(fused, rows, dim, row_pitch, indices, index_bytes,
                                                                 n_indices, offsets, n_bags, out,
+                                                                g_sls_nontemporal.load(std::memory_order_relaxed) != 0,
                                                                 static_cast<hipStream_t>(hip_stream));
     return err == hipSuccess ? E4Q_OK : fail_launch(err);
+}
+
+int e4q_set_option(const char* name, int64_t value)
+{
+    std::atomic<int64_t>* opt = find_option(name);
+    if (!opt || opt == &g_greedy_layout_chosen) return E4Q_ERR_BAD_OPTION;
+    if (opt == &g_greedy_layout ? !layout_value_ok(value) : (value != 0 && value != 1)) return E4Q_ERR_BAD_OPTION;
+    opt->store(value, std::memory_order_relaxed);
+    return E4Q_OK;
+}
+
+int64_t e4q_get_option(const char* name)
+{
+    std::atomic<int64_t>* opt = find_option(name);
+    return opt ? opt->load(std::memory_order_relaxed) : (int64_t)E4Q_ERR_BAD_OPTION;
 }
 
 const char* e4q_strerror(int code)
@@ -367,12 +430,13 @@ const char* e4q_strerror(int code)
         case E4Q_ERR_BAD_DTYPE: return "dtype must be E4Q_F32 (0) or E4Q_F16 (1); index_bytes must be 4 or 8";
         case E4Q_ERR_LAUNCH: return "HIP reported an error at kernel launch (see e4q_last_hip_error)";
         case E4Q_ERR_BAD_ALIGNMENT: return "a pointer is not aligned to its element size";
+        case E4Q_ERR_BAD_OPTION: return "unknown diagnostic option, a value it does not take, or a forced layout that does not fit the call's dimension";
         default: return "unknown e4q error code";
     }
 }
 
 const char* e4q_last_hip_error(void) { return g_hip_error; }
 
-int e4q_version(void) { return 200; }  // 0.2.0
+int e4q_version(void) { return 300; }  // 0.3.0
 
 }  // extern "C"

@@ -89,7 +89,8 @@ hipError_t launch_fuse_rows(const uint8_t* codes, const uint16_t* scale_f16, con
                             int32_t dim, int64_t row_pitch, uint8_t* fused, hipStream_t stream);
 hipError_t launch_sparse_lengths_sum_fused(const uint8_t* fused, int64_t rows, int32_t dim, int64_t row_pitch,
                                            const void* indices, int32_t index_bytes, int64_t n_indices,
-                                           const int64_t* offsets, int64_t n_bags, float* out, hipStream_t stream);
+                                           const int64_t* offsets, int64_t n_bags, float* out, bool nontemporal,
+                                           hipStream_t stream);
 hipError_t launch_dequantize(const uint8_t* codes, const uint16_t* scale_f16, const uint16_t* bias_f16,
                              int64_t rows, int32_t dim, int32_t nbits, float* out, hipStream_t stream);
 

@@ -221,7 +221,8 @@ inline hipError_t launch_greedy_rpl_group(const GreedyGroup& g, hipStream_t stre
     return hipGetLastError();
 }
 
-// Host-side launcher for one (D, Tin) instantiation.
+// Host-side launcher for one (D, Tin) instantiation.  One 64-thread workgroup per 64 rows: the grid has
+// as many work-items as the table has rows (rounded up), at most 2^31 + 63, which one grid dimension holds.
 template <int D, typename Tin>
 inline hipError_t launch_greedy_rpl(const GreedyArgs& a, hipStream_t stream)
 {

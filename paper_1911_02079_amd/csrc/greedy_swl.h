@@ -24,6 +24,7 @@
 #pragma once
 
 #include "e4q_device.h"
+#include "e4q_index.h"
 #include "e4q_launch.h"
 
 namespace e4q {
@@ -90,7 +91,9 @@ __global__ void __launch_bounds__(kSwlBlock) greedy_swl_kernel(GreedyArgs a, int
     static_assert(E % 8 == 0 && (E & (E - 1)) == 0 && (L & (L - 1)) == 0 && L <= 64, "bad layout");
     constexpr int kRowsPerBlock = kSwlBlock / L;
     const int sub = threadIdx.x % L;
-    const int64_t row = (int64_t)blockIdx.x * kRowsPerBlock + threadIdx.x / L;
+    const int64_t row0 = linear_block() * kRowsPerBlock;
+    if (row0 >= a.rows) return;  // padding of a folded grid (no barrier in this kernel)
+    const int64_t row = row0 + threadIdx.x / L;
     const bool live = row < a.rows;
     const int64_t r = live ? row : a.rows - 1;  // tail groups redo the last row and store nothing
     const int base = sub * E;
@@ -176,7 +179,7 @@ inline hipError_t launch_greedy_swl(const GreedyArgs& a, int32_t d, hipStream_t 
 {
     constexpr int kRowsPerBlock = kSwlBlock / L;
     const int64_t blocks = (a.rows + kRowsPerBlock - 1) / kRowsPerBlock;
-    hipLaunchKernelGGL((greedy_swl_kernel<E, L, Tin, MASK>), dim3((unsigned)blocks), dim3(kSwlBlock), 0, stream, a, d);
+    hipLaunchKernelGGL((greedy_swl_kernel<E, L, Tin, MASK>), grid_for(blocks), dim3(kSwlBlock), 0, stream, a, d);
     return hipGetLastError();
 }
 

@@ -1,6 +1,7 @@
 // Codebook kernels that are not specialised by dimension: the any-dimension Lloyd kernel, the
 // dispatcher, and the codebook de-quantizer.
 #include "kmeans16.h"
+#include "e4q_index.h"
 
 namespace e4q {
 
@@ -215,15 +216,16 @@ hipError_t launch_kmeans16(const KMeansArgs& a, int dtype, int32_t dim, hipStrea
 constexpr int kCbBlock = 256;
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
+template <bool WIDE>
 __global__ void __launch_bounds__(kCbBlock) dequantize_codebook_w4_kernel(const uint16_t* __restrict__ idx,
                                                                           const uint16_t* __restrict__ cb,
                                                                           int64_t n_quads, uint32_t quads_per_row,
                                                                           floatx4* __restrict__ out)
 {
-    // one group of four elements per thread, no loop (the host keeps n_quads below 2^32)
-    const int64_t w = (int64_t)blockIdx.x * kCbBlock + threadIdx.x;
+    // one group of four elements per thread, no loop
+    const int64_t w = linear_block() * kCbBlock + threadIdx.x;
     if (w >= n_quads) return;
-    const int64_t row = (int64_t)((uint32_t)w / quads_per_row);
+    const int64_t row = group_of<WIDE>(w, quads_per_row);
     const uint16_t* book = cb + row * kK;
     const uint32_t q = __builtin_nontemporal_load(idx + w);
     floatx4 v;
@@ -240,8 +242,8 @@ __global__ void __launch_bounds__(kCbBlock) dequantize_codebook_any_kernel(const
                                                                            float* __restrict__ out)
 {
     const uint32_t nbytes = (dim + 1) / 2;
-    const int64_t stride = (int64_t)gridDim.x * kCbBlock;
-    for (int64_t e = (int64_t)blockIdx.x * kCbBlock + threadIdx.x; e < n_elems; e += stride) {
+    const int64_t stride = (int64_t)gridDim.x * gridDim.y * kCbBlock;
+    for (int64_t e = linear_block() * kCbBlock + threadIdx.x; e < n_elems; e += stride) {
         const int64_t row = e / dim;
         const uint32_t k = (uint32_t)(e - row * dim);
         const uint32_t byte = idx[row * nbytes + k / 2];
@@ -258,11 +260,11 @@ __global__ void __launch_bounds__(kCbBlock) dequantize_codebook_flat4_kernel(con
                                                                              int64_t n_elems, uint32_t dim,
                                                                              float* __restrict__ out)
 {
-    const int64_t e0 = ((int64_t)blockIdx.x * kCbBlock + threadIdx.x) * 4;
+    const int64_t e0 = (linear_block() * kCbBlock + threadIdx.x) * 4;
     if (e0 >= n_elems) return;
     const uint32_t nbytes = (dim + 1) / 2;
-    int64_t row = WIDE ? e0 / dim : (int64_t)((uint32_t)e0 / dim);
-    uint32_t k = (uint32_t)(e0 - row * dim);
+    int64_t row = group_of<WIDE>(e0, dim);
+    uint32_t k = offset_in_group(e0, row, dim);
     float v[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -290,26 +292,31 @@ hipError_t launch_dequantize_codebook(const uint8_t* idx, const uint16_t* centro
 {
     const int64_t n_quads = rows * (dim / 4);
     const bool fast = dim % 4 == 0 && reinterpret_cast<uintptr_t>(idx) % 2 == 0 &&
-                      reinterpret_cast<uintptr_t>(out) % 16 == 0 && n_quads <= 0xffffffffLL;
+                      reinterpret_cast<uintptr_t>(out) % 16 == 0 && blocks_for(n_quads, kCbBlock) >= 0;
     if (fast) {
-        const int64_t blocks = (n_quads + kCbBlock - 1) / kCbBlock;
-        hipLaunchKernelGGL(dequantize_codebook_w4_kernel, dim3((unsigned)blocks), dim3(kCbBlock), 0, stream,
-                           reinterpret_cast<const uint16_t*>(idx), centroids_f16, n_quads, (uint32_t)(dim / 4),
-                           reinterpret_cast<floatx4*>(out));
+        const dim3 grid = grid_for(blocks_for(n_quads, kCbBlock)), block(kCbBlock);
+        if (needs_wide_index(n_quads))
+            hipLaunchKernelGGL(dequantize_codebook_w4_kernel<true>, grid, block, 0, stream,
+                               reinterpret_cast<const uint16_t*>(idx), centroids_f16, n_quads, (uint32_t)(dim / 4),
+                               reinterpret_cast<floatx4*>(out));
+        else
+            hipLaunchKernelGGL(dequantize_codebook_w4_kernel<false>, grid, block, 0, stream,
+                               reinterpret_cast<const uint16_t*>(idx), centroids_f16, n_quads, (uint32_t)(dim / 4),
+                               reinterpret_cast<floatx4*>(out));
     } else {
         const int64_t n_elems = rows * dim;
-        const int64_t blocks4 = ((n_elems + 3) / 4 + kCbBlock - 1) / kCbBlock;
-        if (reinterpret_cast<uintptr_t>(out) % 16 == 0 && blocks4 <= 0x7fffffffLL) {
-            if (n_elems > 0xffffffffLL)
-                hipLaunchKernelGGL(dequantize_codebook_flat4_kernel<true>, dim3((unsigned)blocks4), dim3(kCbBlock), 0,
+        const int64_t blocks4 = blocks_for((n_elems + 3) / 4, kCbBlock);
+        if (reinterpret_cast<uintptr_t>(out) % 16 == 0 && blocks4 >= 0) {
+            if (needs_wide_index(n_elems))
+                hipLaunchKernelGGL(dequantize_codebook_flat4_kernel<true>, grid_for(blocks4), dim3(kCbBlock), 0,
                                    stream, idx, centroids_f16, n_elems, (uint32_t)dim, out);
             else
-                hipLaunchKernelGGL(dequantize_codebook_flat4_kernel<false>, dim3((unsigned)blocks4), dim3(kCbBlock), 0,
+                hipLaunchKernelGGL(dequantize_codebook_flat4_kernel<false>, grid_for(blocks4), dim3(kCbBlock), 0,
                                    stream, idx, centroids_f16, n_elems, (uint32_t)dim, out);
         } else {
             int64_t blocks = (n_elems + kCbBlock - 1) / kCbBlock;
-            if (blocks > 0x7fffffffLL) blocks = 0x7fffffffLL;  // the kernel loops over what is left
-            hipLaunchKernelGGL(dequantize_codebook_any_kernel, dim3((unsigned)blocks), dim3(kCbBlock), 0, stream, idx,
+            if (blocks > kMaxGridX) blocks = kMaxGridX;  // the kernel loops over what is left
+            hipLaunchKernelGGL(dequantize_codebook_any_kernel, grid_for(blocks), dim3(kCbBlock), 0, stream, idx,
                                centroids_f16, n_elems, (uint32_t)dim, out);
         }
     }

@@ -9,6 +9,7 @@
 // flight per thread; the accumulation order stays the index order.  Indices outside [0, rows) add
 // nothing; offsets are clamped to [0, n_indices], so no input can cause an out-of-range read.
 #include "e4q_device.h"
+#include "e4q_index.h"
 #include "e4q_launch.h"
 
 namespace e4q {
@@ -52,10 +53,11 @@ __global__ void __launch_bounds__(kSlsBlock) sls_w8_kernel(const uint32_t* __res
                                                            int64_t n_indices, const int64_t* __restrict__ offsets,
                                                            int64_t n_bags, floatx4* __restrict__ out)
 {
-    const int64_t t = (int64_t)blockIdx.x * kSlsBlock + threadIdx.x;
-    const int64_t bag = (n_bags * wpr <= 0xffffffffLL) ? (int64_t)((uint32_t)t / wpr) : t / wpr;
-    if (bag >= n_bags) return;
-    const uint32_t word = (uint32_t)(t - bag * wpr);
+    const int64_t t = linear_block() * kSlsBlock + threadIdx.x;
+    const int64_t n_threads = n_bags * wpr;
+    if (t >= n_threads) return;  // tested in 64 bits: the padded grid may run past 2^32
+    const int64_t bag = group_of(t, n_threads, wpr);
+    const uint32_t word = offset_in_group(t, bag, wpr);
     const int64_t lo = offsets[bag], hi = offsets[bag + 1];
     const int64_t begin = lo < 0 ? 0 : (lo > n_indices ? n_indices : lo);
     const int64_t end = hi < begin ? begin : (hi > n_indices ? n_indices : hi);
@@ -134,10 +136,11 @@ __global__ void __launch_bounds__(kSlsBlock) sls_bytes_kernel(const uint8_t* __r
                                                               int64_t n_bags, float* __restrict__ out)
 {
     const uint32_t wpr = (dim + 7) / 8, nbytes = (dim + 1) / 2;
-    const int64_t t = (int64_t)blockIdx.x * kSlsBlock + threadIdx.x;
-    const int64_t bag = t / wpr;
-    if (bag >= n_bags) return;
-    const uint32_t word = (uint32_t)(t - bag * wpr);
+    const int64_t t = linear_block() * kSlsBlock + threadIdx.x;
+    const int64_t n_threads = n_bags * wpr;
+    if (t >= n_threads) return;
+    const int64_t bag = group_of(t, n_threads, wpr);
+    const uint32_t word = offset_in_group(t, bag, wpr);
     sls_bytes_body<Tidx>([&](int64_t r) {
         SlsRow g = {0u, 0.0f, 0.0f};
         if (r >= 0 && r < rows) {
@@ -160,10 +163,11 @@ __global__ void __launch_bounds__(kSlsBlock) sls_fused_h8_kernel(const uint8_t* 
 {
     const uint32_t wpr = (dim + 7) / 8, nbytes = (dim + 1) / 2;
     const uint32_t params_at = (nbytes + 1u) & ~1u;
-    const int64_t t = (int64_t)blockIdx.x * kSlsBlock + threadIdx.x;
-    const int64_t bag = t / wpr;
-    if (bag >= n_bags) return;
-    const uint32_t word = (uint32_t)(t - bag * wpr);
+    const int64_t t = linear_block() * kSlsBlock + threadIdx.x;
+    const int64_t n_threads = n_bags * wpr;
+    if (t >= n_threads) return;
+    const int64_t bag = group_of(t, n_threads, wpr);
+    const uint32_t word = offset_in_group(t, bag, wpr);
     sls_bytes_body<Tidx>([&](int64_t r) {
         SlsRow g = {0u, 0.0f, 0.0f};
         if (r >= 0 && r < rows) {
@@ -192,7 +196,7 @@ __global__ void __launch_bounds__(kSlsBlock) fuse_rows_any_kernel(const uint8_t*
                                                                   uint32_t nbytes, uint32_t pitch,
                                                                   uint8_t* __restrict__ fused)
 {
-    const int64_t t = (int64_t)blockIdx.x * kSlsBlock + threadIdx.x;
+    const int64_t t = linear_block() * kSlsBlock + threadIdx.x;
     const int64_t r = t / pitch;
     if (r >= rows) return;
     const uint32_t k = (uint32_t)(t - r * pitch);
@@ -211,7 +215,7 @@ __global__ void __launch_bounds__(kSlsBlock) fuse_rows_w_kernel(const uint32_t* 
                                                                 uint32_t wpr, uint32_t pitch_words,
                                                                 uint32_t* __restrict__ fused)
 {
-    const int64_t t = (int64_t)blockIdx.x * kSlsBlock + threadIdx.x;
+    const int64_t t = linear_block() * kSlsBlock + threadIdx.x;
     const int64_t r = t / pitch_words;
     if (r >= rows) return;
     const uint32_t k = (uint32_t)(t - r * pitch_words);
@@ -228,21 +232,21 @@ hipError_t launch_fuse_rows(const uint8_t* codes, const uint16_t* sc, const uint
     const bool words = nbytes % 4 == 0 && row_pitch % 4 == 0 && reinterpret_cast<uintptr_t>(codes) % 4 == 0 &&
                        reinterpret_cast<uintptr_t>(fused) % 4 == 0;
     const int64_t threads = words ? rows * (row_pitch / 4) : rows * row_pitch;
-    const int64_t blocks = (threads + kSlsBlock - 1) / kSlsBlock;
-    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    const int64_t blocks = blocks_for(threads, kSlsBlock);
+    if (blocks < 0) return hipErrorInvalidValue;
     if (words)
-        hipLaunchKernelGGL(fuse_rows_w_kernel, dim3((unsigned)blocks), dim3(kSlsBlock), 0, stream,
+        hipLaunchKernelGGL(fuse_rows_w_kernel, grid_for(blocks), dim3(kSlsBlock), 0, stream,
                            reinterpret_cast<const uint32_t*>(codes), sc, bi, rows, nbytes / 4,
                            (uint32_t)(row_pitch / 4), reinterpret_cast<uint32_t*>(fused));
     else
-        hipLaunchKernelGGL(fuse_rows_any_kernel, dim3((unsigned)blocks), dim3(kSlsBlock), 0, stream, codes, sc, bi,
+        hipLaunchKernelGGL(fuse_rows_any_kernel, grid_for(blocks), dim3(kSlsBlock), 0, stream, codes, sc, bi,
                            rows, nbytes, (uint32_t)row_pitch, fused);
     return hipGetLastError();
 }
 
 // Lookup over fused records; dim % 8 == 0, pitch % 4 == 0, 4-byte aligned records, 16-byte aligned out.
 // One thread owns WPT consecutive code words (8 * WPT elements) of one bag.
-template <typename Tidx, int WPT>
+template <typename Tidx, int WPT, bool NT>
 __global__ void __launch_bounds__(kSlsBlock) sls_fused_w8_kernel(const uint32_t* __restrict__ fused, int64_t rows,
                                                                  uint32_t wpr, uint32_t pitch_words,
                                                                  const Tidx* __restrict__ indices, int64_t n_indices,
@@ -251,10 +255,11 @@ __global__ void __launch_bounds__(kSlsBlock) sls_fused_w8_kernel(const uint32_t*
 {
     typedef uint32_t words_t __attribute__((ext_vector_type(WPT), aligned(4)));
     const uint32_t tpb = wpr / WPT;  // threads per bag
-    const int64_t t = (int64_t)blockIdx.x * kSlsBlock + threadIdx.x;
-    const int64_t bag = (n_bags * tpb <= 0xffffffffLL) ? (int64_t)((uint32_t)t / tpb) : t / tpb;
-    if (bag >= n_bags) return;
-    const uint32_t word = (uint32_t)(t - bag * tpb) * WPT;
+    const int64_t t = linear_block() * kSlsBlock + threadIdx.x;
+    const int64_t n_threads = n_bags * tpb;
+    if (t >= n_threads) return;  // tested in 64 bits: the padded grid may run past 2^32
+    const int64_t bag = group_of(t, n_threads, tpb);
+    const uint32_t word = offset_in_group(t, bag, tpb) * WPT;
     const int64_t lo = offsets[bag], hi = offsets[bag + 1];
     const int64_t begin = lo < 0 ? 0 : (lo > n_indices ? n_indices : lo);
     const int64_t end = hi < begin ? begin : (hi > n_indices ? n_indices : hi);
@@ -266,15 +271,21 @@ __global__ void __launch_bounds__(kSlsBlock) sls_fused_w8_kernel(const uint32_t*
     auto gather = [&](Tidx idx) {
         const int64_t r = (int64_t)idx;
         const bool ok = r >= 0 && r < rows;
-        const uint32_t* rec = fused + (ok ? r : 0) * pitch_words;
         Rec g;
-        const uint32_t sb = ok ? rec[wpr] : 0u;  // scale and bias 0: the row adds +0
-        if constexpr (WPT == 1) {
-            g.c[0] = rec[word];
-        } else {
-            const words_t v = *reinterpret_cast<const words_t*>(rec + word);
+        uint32_t sb = 0u;  // scale and bias 0 and codes 0: the row adds +0
 #pragma unroll
-            for (int w = 0; w < WPT; ++w) g.c[w] = v[w];
+        for (int w = 0; w < WPT; ++w) g.c[w] = 0u;
+        if (ok) {  // nothing is read for an index outside the table (which may be empty: fused == NULL)
+            const uint32_t* rec = fused + r * pitch_words;
+            sb = NT ? __builtin_nontemporal_load(rec + wpr) : rec[wpr];
+            if constexpr (WPT == 1) {
+                g.c[0] = NT ? __builtin_nontemporal_load(rec + word) : rec[word];
+            } else {
+                const words_t* pv = reinterpret_cast<const words_t*>(rec + word);
+                const words_t v = NT ? __builtin_nontemporal_load(pv) : *pv;
+#pragma unroll
+                for (int w = 0; w < WPT; ++w) g.c[w] = v[w];
+            }
         }
         g.s = f16_bits_to_float((uint16_t)(sb & 0xffffu));
         g.b = f16_bits_to_float((uint16_t)(sb >> 16));
@@ -312,7 +323,7 @@ __global__ void __launch_bounds__(kSlsBlock) sls_fused_w8_kernel(const uint32_t*
 template <typename Tidx>
 static hipError_t launch_sls_fused_t(const uint8_t* fused, int64_t rows, int32_t dim, int64_t pitch,
                                      const void* indices, int64_t n_indices, const int64_t* offsets, int64_t n_bags,
-                                     float* out, hipStream_t stream)
+                                     float* out, bool nontemporal, hipStream_t stream)
 {
     const bool fast = dim % 8 == 0 && pitch % 4 == 0 && reinterpret_cast<uintptr_t>(fused) % 4 == 0 &&
                       reinterpret_cast<uintptr_t>(out) % 16 == 0;
@@ -322,31 +333,39 @@ static hipError_t launch_sls_fused_t(const uint8_t* fused, int64_t rows, int32_t
         wpt = wpr % 2 == 0 ? 2 : 1;  // 8-byte gathers measured 6 % faster than 4-byte ones, 16-byte ones no better
     }
     const int64_t threads = fast ? n_bags * (wpr / wpt) : n_bags * ((dim + 7) / 8);
-    const int64_t blocks = (threads + kSlsBlock - 1) / kSlsBlock;
-    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
-    const dim3 grid((unsigned)blocks), block(kSlsBlock);
+    const int64_t blocks = blocks_for(threads, kSlsBlock);
+    if (blocks < 0) return hipErrorInvalidValue;
+    const dim3 grid = grid_for(blocks), block(kSlsBlock);
     const uint32_t* f32 = reinterpret_cast<const uint32_t*>(fused);
     const Tidx* idx = static_cast<const Tidx*>(indices);
     floatx4* o4 = reinterpret_cast<floatx4*>(out);
     if (!fast)
         hipLaunchKernelGGL(sls_fused_h8_kernel<Tidx>, grid, block, 0, stream, fused, rows, (uint32_t)dim, pitch, idx,
                            n_indices, offsets, n_bags, out);
+    else if (wpt == 2 && nontemporal)
+        hipLaunchKernelGGL((sls_fused_w8_kernel<Tidx, 2, true>), grid, block, 0, stream, f32, rows, (uint32_t)wpr,
+                           (uint32_t)(pitch / 4), idx, n_indices, offsets, n_bags, o4);
     else if (wpt == 2)
-        hipLaunchKernelGGL((sls_fused_w8_kernel<Tidx, 2>), grid, block, 0, stream, f32, rows, (uint32_t)wpr,
+        hipLaunchKernelGGL((sls_fused_w8_kernel<Tidx, 2, false>), grid, block, 0, stream, f32, rows, (uint32_t)wpr,
+                           (uint32_t)(pitch / 4), idx, n_indices, offsets, n_bags, o4);
+    else if (nontemporal)
+        hipLaunchKernelGGL((sls_fused_w8_kernel<Tidx, 1, true>), grid, block, 0, stream, f32, rows, (uint32_t)wpr,
                            (uint32_t)(pitch / 4), idx, n_indices, offsets, n_bags, o4);
     else
-        hipLaunchKernelGGL((sls_fused_w8_kernel<Tidx, 1>), grid, block, 0, stream, f32, rows, (uint32_t)wpr,
+        hipLaunchKernelGGL((sls_fused_w8_kernel<Tidx, 1, false>), grid, block, 0, stream, f32, rows, (uint32_t)wpr,
                            (uint32_t)(pitch / 4), idx, n_indices, offsets, n_bags, o4);
     return hipGetLastError();
 }
 
 hipError_t launch_sparse_lengths_sum_fused(const uint8_t* fused, int64_t rows, int32_t dim, int64_t pitch,
                                            const void* indices, int32_t index_bytes, int64_t n_indices,
-                                           const int64_t* offsets, int64_t n_bags, float* out, hipStream_t stream)
+                                           const int64_t* offsets, int64_t n_bags, float* out, bool nontemporal,
+                                           hipStream_t stream)
 {
-    return index_bytes == 4
-               ? launch_sls_fused_t<int32_t>(fused, rows, dim, pitch, indices, n_indices, offsets, n_bags, out, stream)
-               : launch_sls_fused_t<int64_t>(fused, rows, dim, pitch, indices, n_indices, offsets, n_bags, out, stream);
+    return index_bytes == 4 ? launch_sls_fused_t<int32_t>(fused, rows, dim, pitch, indices, n_indices, offsets, n_bags,
+                                                          out, nontemporal, stream)
+                            : launch_sls_fused_t<int64_t>(fused, rows, dim, pitch, indices, n_indices, offsets, n_bags,
+                                                          out, nontemporal, stream);
 }
 
 template <typename Tidx>
@@ -357,15 +376,15 @@ static hipError_t launch_sls_t(const uint8_t* codes, const uint16_t* sc, const u
     const bool fast = dim % 8 == 0 && reinterpret_cast<uintptr_t>(codes) % 4 == 0 &&
                       reinterpret_cast<uintptr_t>(out) % 16 == 0;
     const int64_t threads = fast ? n_bags * (dim / 8) : n_bags * ((dim + 7) / 8);
-    const int64_t blocks = (threads + kSlsBlock - 1) / kSlsBlock;
-    if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    const int64_t blocks = blocks_for(threads, kSlsBlock);
+    if (blocks < 0) return hipErrorInvalidValue;
     if (fast)
-        hipLaunchKernelGGL(sls_w8_kernel<Tidx>, dim3((unsigned)blocks), dim3(kSlsBlock), 0, stream,
+        hipLaunchKernelGGL(sls_w8_kernel<Tidx>, grid_for(blocks), dim3(kSlsBlock), 0, stream,
                            reinterpret_cast<const uint32_t*>(codes), sc, bi, rows, (uint32_t)(dim / 8),
                            static_cast<const Tidx*>(indices), n_indices, offsets, n_bags,
                            reinterpret_cast<floatx4*>(out));
     else
-        hipLaunchKernelGGL(sls_bytes_kernel<Tidx>, dim3((unsigned)blocks), dim3(kSlsBlock), 0, stream, codes, sc, bi,
+        hipLaunchKernelGGL(sls_bytes_kernel<Tidx>, grid_for(blocks), dim3(kSlsBlock), 0, stream, codes, sc, bi,
                            rows, (uint32_t)dim, static_cast<const Tidx*>(indices), n_indices, offsets, n_bags, out);
     return hipGetLastError();
 }

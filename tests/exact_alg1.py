@@ -1,8 +1,8 @@
 """Algorithm 1, Eq. 1 and Eq. 2 of arXiv 1911.02079 in exact rational arithmetic.
 
 A pin for the oracle that shares nothing with it: Python `Fraction`s, no rounding
-anywhere except the round() of Eq. 1 itself, and the while-loop of Algorithm 1
-with its own stopping test (evaluated exactly).  On inputs built so that every
+anywhere except the round() of Eq. 1 itself, and Algorithm 1's search written as a
+walk over integer lattice coordinates with its stopping test evaluated exactly.  On inputs built so that every
 floating-point operation of the oracle is exact (integer lattices, see
 `lattice_row`), oracle and this file must agree on the returned range, on the
 loss and on every non-tie code.
@@ -51,34 +51,46 @@ def loss(X, xmin: Fraction, xmax: Fraction, nbits: int = 4) -> Fraction:
 
 
 def greedy(X, b: int, r: Fraction, literal: bool = False, nbits: int = 4):
-    """Algorithm 1.  `literal=False` stores the pair (cur_min, cur_max) with every improvement;
-    `literal=True` updates only the bound that moved, as the printed listing does.
-    Returns (xmin, xmax, loss, n_trips, largest loss evaluated)."""
+    """The search of Algorithm 1 as a walk on the lattice of clipping ranges.
+
+    Node (i, j) is the range [lowest + i*w, highest - j*w] with w = (highest - lowest)/b, so its
+    width is (b - i - j)*w.  The walk starts at (0, 0) and, while the width of the node it stands
+    on still exceeds b*(1 - r)*w (Algorithm 1's stopping test, here stated on the width and
+    evaluated exactly; a row of equal values has w = 0 and never moves), scores the two
+    neighbours (i + 1, j) and (i, j + 1) with Eq. 2 and steps to the one whose error is strictly
+    smaller, to (i, j + 1) on a tie.  The answer is the node with the smallest error met, the
+    earliest one among equals.  `literal=True` keeps the printed bookkeeping instead: an
+    improvement found by raising the lower bound records only i, one found by lowering the
+    upper bound records only j, and the answer combines the two records.
+    Returns (xmin, xmax, error of the best node, moves made, largest error evaluated)."""
     X = [Fraction(x) for x in X]
-    xmin = cur_min = min(X)
-    xmax = cur_max = max(X)
-    best = loss(X, xmin, xmax, nbits)
-    stepsize = (xmax - xmin) / b
-    min_steps = b * (1 - r) * stepsize
-    trips, biggest = 0, best
-    while cur_min + min_steps < cur_max:
-        trips += 1
-        loss_l = loss(X, cur_min + stepsize, cur_max, nbits)
-        loss_r = loss(X, cur_min, cur_max - stepsize, nbits)
-        biggest = max(biggest, loss_l, loss_r)
-        if loss_l < loss_r:
-            cur_min = cur_min + stepsize
-            if loss_l < best:
-                best, xmin = loss_l, cur_min
+    lowest, highest = min(X), max(X)
+    w = (highest - lowest) / b
+
+    def node_error(i, j):
+        return loss(X, lowest + i * w, highest - j * w, nbits)
+
+    i = j = 0
+    keep_i = keep_j = 0
+    smallest = largest = node_error(0, 0)
+    moves = 0
+    while (b - i - j) * w > b * (1 - r) * w:
+        moves += 1
+        up, down = node_error(i + 1, j), node_error(i, j + 1)
+        largest = max(largest, up, down)
+        if up < down:
+            i += 1
+            if up < smallest:
+                smallest, keep_i = up, i
                 if not literal:
-                    xmax = cur_max
+                    keep_j = j
         else:
-            cur_max = cur_max - stepsize
-            if loss_r < best:
-                best, xmax = loss_r, cur_max
+            j += 1
+            if down < smallest:
+                smallest, keep_j = down, j
                 if not literal:
-                    xmin = cur_min
-    return xmin, xmax, best, trips, biggest
+                    keep_i = i
+    return lowest + keep_i * w, highest - keep_j * w, smallest, moves, largest
 
 
 def lattice_row(rng: np.random.Generator, d: int, b: int, shift: int = 0, outliers: int = 2,

@@ -32,7 +32,7 @@ def test_header_declares_the_expected_entry_points():
     for must in ["e4q_quantize_rowwise_greedy", "e4q_dequantize", "e4q_quantize_rowwise_greedy_batch",
                  "e4q_greedy_iterations", "e4q_strerror", "e4q_last_hip_error", "e4q_version",
                  "e4q_quantize_rowwise_kmeans16", "e4q_dequantize_codebook", "e4q_sparse_lengths_sum", "e4q_fuse_rows",
-                 "e4q_sparse_lengths_sum_fused", "e4q_fused_row_bytes"]:
+                 "e4q_sparse_lengths_sum_fused", "e4q_fused_row_bytes", "e4q_set_option", "e4q_get_option"]:
         assert must in names
 
 
@@ -43,7 +43,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_version_and_strerror(lib):
     assert lib.e4q_version() >= 100
-    for code in range(0, -8, -1):
+    for code in range(0, -9, -1):
         assert lib.e4q_strerror(code)
     assert b"unknown" in lib.e4q_strerror(-99)
     assert lib.e4q_last_hip_error() == b""
@@ -156,6 +156,60 @@ def test_validation_rejects_bad_arguments_before_any_launch(lib):
     assert lib.e4q_quantize_rowwise_greedy_batch(descs, 0, 4, 100, 0.16, None) == 0
     assert lib.e4q_quantize_rowwise_greedy_batch(None, 2, 4, 100, 0.16, None) == -1
     assert lib.e4q_quantize_rowwise_greedy_batch(descs, 2, 3, 100, 0.16, None) == -3
+
+
+def test_diagnostic_options(lib):
+    """Options are validated on the host; a forced layout that cannot hold a row is refused before
+    anything is launched (so this is safe without a GPU)."""
+    lib.e4q_set_option.argtypes = [ctypes.c_char_p, ctypes.c_int64]
+    lib.e4q_get_option.argtypes = [ctypes.c_char_p]
+    lib.e4q_get_option.restype = ctypes.c_int64
+    for name in (b"greedy_layout", b"kmeans_force_scan", b"sls_nontemporal"):
+        assert lib.e4q_get_option(name) == 0
+    assert lib.e4q_set_option(b"no_such_option", 1) == -8
+    assert lib.e4q_get_option(b"no_such_option") == -8
+    assert lib.e4q_set_option(None, 1) == -8
+    assert lib.e4q_set_option(b"kmeans_force_scan", 2) == -8
+    assert lib.e4q_set_option(b"sls_nontemporal", -1) == -8
+    for bad in [(8 << 8) | 3, (8 << 8) | 128, (12 << 8) | 4, (128 << 8) | 64, (8 << 8), 2, -1]:
+        assert lib.e4q_set_option(b"greedy_layout", bad) == -8
+        assert lib.e4q_get_option(b"greedy_layout") == 0
+    p = ctypes.c_void_p(0x1000)
+    q = lib.e4q_quantize_rowwise_greedy
+    try:
+        assert lib.e4q_set_option(b"greedy_layout", (8 << 8) | 4) == 0      # holds 32 elements per row
+        assert lib.e4q_get_option(b"greedy_layout") == (8 << 8) | 4
+        assert q(p, 0, 10, 64, 64, 4, 200, 0.16, p, p, p, None) == -8
+        assert q(p, 0, 10, 64, 64, 3, 200, 0.16, p, p, p, None) == -3       # ordinary validation comes first
+        assert lib.e4q_set_option(b"greedy_layout", 1) == 0                  # one row per lane: dim <= 128
+        assert q(p, 0, 10, 256, 256, 4, 200, 0.16, p, p, p, None) == -8
+        from paper_1911_02079_amd.binding import TableDesc
+
+        descs = (TableDesc * 2)()
+        for d, dim in zip(descs, (64, 200)):
+            d.table, d.dtype, d.dim, d.rows, d.row_stride = 0x1000, 0, dim, 5, dim
+            d.codes, d.scale_f16, d.bias_f16 = 0x1000, 0x1000, 0x1000
+        assert lib.e4q_quantize_rowwise_greedy_batch(descs, 2, 4, 100, 0.16, None) == -8
+    finally:
+        assert lib.e4q_set_option(b"greedy_layout", 0) == 0
+    assert lib.e4q_set_option(b"kmeans_force_scan", 1) == 0 and lib.e4q_get_option(b"kmeans_force_scan") == 1
+    assert lib.e4q_set_option(b"kmeans_force_scan", 0) == 0
+
+
+def test_binding_checks_caller_supplied_outputs():
+    """The checks run before the library is called; CPU tensors are refused first, so the shape and
+    type checks are exercised on the private helper."""
+    import torch
+
+    from paper_1911_02079_amd import binding
+
+    dev = torch.device("cpu")
+    good = torch.empty((4, 32), dtype=torch.uint8)
+    with pytest.raises(ValueError):
+        binding._check_out(good, torch.uint8, (4, 32), torch.device("cpu"), "codes")  # not a GPU tensor
+    assert binding.greedy_layout_value(None) == 0 and binding.greedy_layout_value("rpl") == 1
+    assert binding.greedy_layout_value("64,2") == (64 << 8) | 2 and binding.greedy_layout_value((8, 16)) == (8 << 8) | 16
+    del dev
 
 
 def test_binding_refuses_cpu_tensors():

@@ -203,18 +203,21 @@ def clumped_rows(rows, dim, seed):
 
 
 @pytest.mark.parametrize("dim", [24, 50, 64, 101, 128, 200])
-def test_clumped_rows_and_forced_scan(e4q, oracle_lib, dim, monkeypatch):
+def test_clumped_rows_and_forced_scan(e4q, oracle_lib, dim):
     """The bisection over ordered centres and the 16-centre scan give the oracle's result on rows with
     coinciding and nearly coinciding centres; the scan is forced through the diagnostic switch."""
     t = torch.from_numpy(clumped_rows(4_099, dim, 900 + dim)).cuda()
     idx, cent = compare(e4q, oracle_lib, t, 6, "clumped rows, bisection")
-    monkeypatch.setenv("E4Q_KMEANS_FORCE_SCAN", "1")
-    idx2, cent2 = compare(e4q, oracle_lib, t, 6, "clumped rows, forced scan")
-    assert torch.equal(idx, idx2) and torch.equal(cent.view(torch.int16), cent2.view(torch.int16))
     from paper_1911_02079_amd import synth
 
-    g = synth.mixture_table(5_003, dim, device="cuda")
-    compare(e4q, oracle_lib, g, 20, "mixture rows, forced scan")
+    e4q.set_option("kmeans_force_scan", 1)
+    try:
+        idx2, cent2 = compare(e4q, oracle_lib, t, 6, "clumped rows, forced scan")
+        assert torch.equal(idx, idx2) and torch.equal(cent.view(torch.int16), cent2.view(torch.int16))
+        g = synth.mixture_table(5_003, dim, device="cuda")
+        compare(e4q, oracle_lib, g, 20, "mixture rows, forced scan")
+    finally:
+        e4q.set_option("kmeans_force_scan", 0)
 
 
 def test_full_config5_mixture_2M_x_64(e4q, oracle_lib):

@@ -143,3 +143,45 @@ def test_full_size_lookup_sampled_bags(e4q, oracle_lib):
         fused = e4q.fuse_rows(codes, scale, bias, dim, pitch)
         assert torch.equal(e4q.sparse_lengths_sum_fused(fused, dim, indices, offsets), out)
         del fused
+
+
+@pytest.mark.parametrize("dim", [128, 64, 8, 13])
+def test_empty_table_with_non_empty_bags_gives_zeros(e4q, dim):
+    """rows == 0: every index is outside the table, so every bag sums to +0 and nothing is read
+    from the (absent) table -- for the three arrays and for fused records, whose pointer is NULL."""
+    say(f"empty table, dim={dim}: 9 bags over 40 indices")
+    codes = torch.empty((0, (dim + 1) // 2), dtype=torch.uint8, device="cuda")
+    scale = torch.empty((0,), dtype=torch.float16, device="cuda")
+    bias = torch.empty((0,), dtype=torch.float16, device="cuda")
+    indices = torch.arange(-3, 37, dtype=torch.int64, device="cuda")
+    offsets = torch.tensor([0, 0, 1, 5, 9, 17, 17, 30, 39, 40], dtype=torch.int64, device="cuda")
+    for idx in (indices, indices.to(torch.int32)):
+        out = torch.full((9, dim), float("nan"), device="cuda")
+        e4q.sparse_lengths_sum(codes, scale, bias, dim, idx, offsets, out=out)
+        torch.cuda.synchronize()
+        assert bool((out == 0).all())
+        pitch = e4q.fused_row_bytes(dim)
+        fused = torch.empty((0, pitch), dtype=torch.uint8, device="cuda")
+        out = torch.full((9, dim), float("nan"), device="cuda")
+        e4q.sparse_lengths_sum_fused(fused, dim, idx, offsets, out=out)
+        torch.cuda.synchronize()
+        assert bool((out == 0).all())
+
+
+def test_non_temporal_gathers_give_the_same_sums(e4q, oracle_lib):
+    from paper_1911_02079_amd import synth
+
+    for dim in (128, 72):
+        t = synth.outlier_table(4_000, dim, seed=60 + dim, device="cuda")
+        codes, scale, bias = e4q.quantize_rowwise_greedy(t, 50, 0.2)
+        indices, offsets = make_bags(4_000, 500, 50, seed=61, bad=30)
+        want = oracle_lib.sparse_lengths_sum(codes.cpu().numpy(), f16_bits(scale), f16_bits(bias), dim, indices, offsets)
+        fused = e4q.fuse_rows(codes, scale, bias, dim)
+        say(f"non-temporal gathers, dim={dim}")
+        try:
+            e4q.set_option("sls_nontemporal", 1)
+            got = e4q.sparse_lengths_sum_fused(fused, dim, torch.from_numpy(indices).cuda(), torch.from_numpy(offsets).cuda())
+            torch.cuda.synchronize()
+        finally:
+            e4q.set_option("sls_nontemporal", 0)
+        assert np.array_equal(got.cpu().numpy().view(np.uint32), want.view(np.uint32))

@@ -320,8 +320,10 @@ def main() -> int:
         q_name, dq_name = ("greedy_rpl_kernel" if rpl else "greedy_swl_kernel"), "dequantize_w4_kernel"
         ops_per_row = greedy_lane_ops_per_row(dim, n_iter)
         out_bytes_per_row = e4q.packed_bytes(dim, nbits) + 4
+        model_cycles = e4q.greedy_layout_cost(rows, dim, n_iter, chosen) if n_iter > 0 else None
         config = {"n_bins": n_bins, "ratio": ratio, "candidate_ranges_per_row": 1 + 2 * n_iter, "nbits": nbits,
                   "layout": layout, "layout_forced": args.layout != "auto",
+                  "layout_model_us": None if model_cycles is None else model_cycles / 2.4e3,
                   "step": "quantize_rowwise_greedy + dequantize, table resident in HBM"}
         metric = f"rows quantized/sec (greedy {nbits}-bit)"
 

@@ -235,6 +235,15 @@ int32_t e4q_greedy_iterations(int32_t n_bins, float ratio);
 int e4q_set_option(const char* name, int64_t value);
 int64_t e4q_get_option(const char* name);
 
+/*
+ * The estimate behind the automatic choice of "greedy_layout": SIMD cycles the greedy search of a
+ * rows x dim table with n_iter trips would take in the given layout (encoding of "greedy_layout",
+ * not 0), from the instruction count of the layout and the issue rates measured on gfx950.  The
+ * library runs the layout with the smallest estimate.  Diagnostic, host-only; negative if the layout
+ * cannot hold a row of `dim` elements or an argument is out of range.
+ */
+double e4q_greedy_layout_cost(int64_t rows, int32_t dim, int32_t n_iter, int64_t layout);
+
 /* Static, human-readable text for a return code (never NULL). */
 const char* e4q_strerror(int code);
 

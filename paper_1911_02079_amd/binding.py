@@ -77,6 +77,8 @@ def load_library() -> ctypes.CDLL:
     lib.e4q_set_option.restype = c.c_int
     lib.e4q_get_option.argtypes = [c.c_char_p]
     lib.e4q_get_option.restype = c.c_int64
+    lib.e4q_greedy_layout_cost.argtypes = [c.c_int64, c.c_int32, c.c_int32, c.c_int64]
+    lib.e4q_greedy_layout_cost.restype = c.c_double
     lib.e4q_strerror.argtypes = [c.c_int]
     lib.e4q_strerror.restype = c.c_char_p
     lib.e4q_last_hip_error.argtypes = []
@@ -141,6 +143,12 @@ def get_option(name: str) -> int:
     if v < 0:
         _check(v)
     return v
+
+
+def greedy_layout_cost(rows: int, dim: int, n_iter: int, layout) -> float:
+    """e4q_greedy_layout_cost: the library's estimate (SIMD cycles) for one layout; negative if it does not fit."""
+    value = layout if isinstance(layout, int) else greedy_layout_value(layout)
+    return float(load_library().e4q_greedy_layout_cost(int(rows), int(dim), int(n_iter), value))
 
 
 def greedy_layout_value(layout) -> int:

@@ -404,6 +404,18 @@ int e4q_sparse_lengths_sum_fused(const uint8_t* fused, int64_t rows, int32_t dim
     return err == hipSuccess ? E4Q_OK : fail_launch(err);
 }
 
+double e4q_greedy_layout_cost(int64_t rows, int32_t dim, int32_t n_iter, int64_t layout)
+{
+    if (rows < 0 || dim <= 0 || dim > E4Q_MAX_DIM || n_iter < 0 || layout == 0 || !layout_value_ok(layout)) return -1.0;
+    if (layout == 1) {
+        if (!(e4q::rpl_supports_dim(dim) || e4q::rpl_tail_supports_dim(dim))) return -1.0;
+        return layout_cost(rows, (dim + 7) / 8 * 8, 1, n_iter, true);
+    }
+    const int32_t e = (int32_t)(layout >> 8), l = (int32_t)(layout & 0xff);
+    if ((int64_t)e * l < dim) return -1.0;
+    return layout_cost(rows, e, l, n_iter, false);
+}
+
 int e4q_set_option(const char* name, int64_t value)
 {
     std::atomic<int64_t>* opt = find_option(name);

@@ -15,7 +15,8 @@
 // Arithmetic per element and round, as the scan defines it: 16 subtractions, 8 three-input minimums,
 // 15 compares, 15 selects and one binary64 add: about 55 operations; the path is bound by VALU issue
 // like the greedy search.  With the centres in order (checked every round) the index comes from a
-// bisection instead, 4 compares and 11 selects.  Rows with dim <= 16 need no clustering (every value
+// bisection instead, 4 compares and 11 selects; with the centres well separated as well (the usual
+// case), from a bisection over the centres that needs only the two distances to the bracketing centres.  Rows with dim <= 16 need no clustering (every value
 // is its own codebook entry).
 #pragma once
 
@@ -25,6 +26,7 @@
 namespace e4q {
 
 constexpr int kK = 16;
+constexpr int kSeparatedBatch = 2;  // values whose nearest-centre bisections run side by side (4 and 8 measure the same)
 
 // First index of the smallest |x - c[k]| (what a scan with a strict '<' finds).  Written as: the
 // smallest distance (3-input minimum instructions), then the lowest index that attains it -- 16
@@ -75,6 +77,113 @@ __device__ __forceinline__ int nearest_centre_sorted(float x, const float (&c)[k
     return (b3 ? 8 * UNIT : 0) | (b2 ? 4 * UNIT : 0) | (b1 ? 2 * UNIT : 0) | (b0 ? UNIT : 0);
 }
 
+// The same index again, cheaper, when the centres are "well separated": strictly increasing with every
+// gap c[k+1] - c[k] above 2^-22 of the row's range (centre_order below).  Then two different centres
+// can never be at the same ROUNDED distance below a value x <= max: equal rounded differences
+// x - c[a] == x - c[b] need |c[a] - c[b]| <= ulp(x - c) <= 2^-23 * range.  So the rounded distances to the
+// centres at or below x strictly decrease towards x, those to the centres above x do not decrease,
+// and the first nearest centre is one of the two that bracket x: the lower one unless the upper one
+// is strictly nearer.  The bracket comes from a bisection over the centres themselves -- t = number
+// of c[0..14] that are <= x -- which keeps the tighter probe on either side as it goes: 4 compares and
+// 19 selects, then 2 subtractions and 1 compare, instead of 16 subtractions, 8 three-input minimums,
+// 4 compares and 11 selects.  The result stays in 0..15 for any input, NaN included.
+// N values are handled side by side, one bisection level at a time: a single value's chain (compare,
+// select, compare, ...) is a dozen dependent instructions, which the two or three waves a SIMD holds
+// cannot cover on their own.  (Measured on gfx950: a select on a condition in a scalar register pair
+// issues every 4.4 cycles, like a compare; selects on VCC would issue every 2.4, but only if VCC was
+// written some ten instructions earlier, and a wave has one VCC, so the conditions stay in register pairs.)
+// `base` is added to the result (the caller's lane offset; base8 = base + 8 * UNIT), so that the first index
+// bit brings it along and the sum of the five terms is two three-input additions.
+template <int UNIT, int N>
+__device__ __forceinline__ void nearest_centre_separated(const float (&x)[N], const float (&c)[kK], int base, int base8,
+                                                         int (&out)[N])
+{
+    bool b3[N], b2[N], b1[N], b0[N];
+    float below[N], above[N], p[N], u0[N], u1[N], v0[N], v1[N], v2[N], v3[N];
+#pragma unroll
+    for (int i = 0; i < N; ++i) b3[i] = x[i] >= c[7];
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        below[i] = b3[i] ? c[7] : -__builtin_inff();
+        above[i] = b3[i] ? c[15] : c[7];
+        p[i] = b3[i] ? c[11] : c[3];
+        u0[i] = b3[i] ? c[9] : c[1];
+        u1[i] = b3[i] ? c[13] : c[5];
+        v0[i] = b3[i] ? c[8] : c[0];
+        v1[i] = b3[i] ? c[10] : c[2];
+        v2[i] = b3[i] ? c[12] : c[4];
+        v3[i] = b3[i] ? c[14] : c[6];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < N; ++i) b2[i] = x[i] >= p[i];
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        below[i] = b2[i] ? p[i] : below[i];
+        above[i] = b2[i] ? above[i] : p[i];
+        p[i] = b2[i] ? u1[i] : u0[i];
+        v0[i] = b2[i] ? v2[i] : v0[i];
+        v1[i] = b2[i] ? v3[i] : v1[i];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < N; ++i) b1[i] = x[i] >= p[i];
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        below[i] = b1[i] ? p[i] : below[i];
+        above[i] = b1[i] ? above[i] : p[i];
+        p[i] = b1[i] ? v1[i] : v0[i];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < N; ++i) b0[i] = x[i] >= p[i];
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        below[i] = b0[i] ? p[i] : below[i];
+        above[i] = b0[i] ? above[i] : p[i];
+    }
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+        // no centre at or below x: below = -inf, the distance to it is +inf and the upper centre, c[0], wins
+        const float dl = x[i] - below[i];
+        const float du = __builtin_fabsf(x[i] - above[i]);
+        out[i] = ((b3[i] ? base8 : base) + (b2[i] ? 4 * UNIT : 0) + (b1[i] ? 2 * UNIT : 0)) +
+                 ((b0[i] ? UNIT : 0) + (dl <= du ? -UNIT : 0));
+    }
+}
+
+template <int UNIT = 1>
+__device__ __forceinline__ int nearest_centre_separated(float x, const float (&c)[kK])
+{
+    const float xs[1] = {x};
+    int out[1];
+    nearest_centre_separated<UNIT, 1>(xs, c, 0, 8 * UNIT, out);
+    return out[0];
+}
+
+// Order of a row's centres: 2 = every gap c[k+1] - c[k] exceeds `min_gap` (well separated), 1 = non-decreasing,
+// 0 = neither.  The smallest rounded gap decides all three (a rounded difference is negative exactly when the
+// real one is).
+__device__ __forceinline__ int centre_order(const float (&c)[kK], float min_gap)
+{
+    float g[kK - 1];
+#pragma unroll
+    for (int k = 0; k + 1 < kK; ++k) g[k] = c[k + 1] - c[k];
+    float m = __builtin_fminf(__builtin_fminf(g[0], g[1]), g[2]);
+#pragma unroll
+    for (int k = 3; k + 1 < kK - 1; k += 2) m = __builtin_fminf(__builtin_fminf(m, g[k]), g[k + 1]);
+    return m > min_gap ? 2 : (m >= 0.0f ? 1 : 0);
+}
+
+// The weakest order among the 64 rows of a wave (a NaN centre makes it 0).
+__device__ __forceinline__ int wave_centre_order(const float (&c)[kK], float min_gap)
+{
+    const int o = centre_order(c, min_gap);
+    if (__builtin_amdgcn_ballot_w64(o < 1) != 0) return 0;
+    return __builtin_amdgcn_ballot_w64(o < 2) != 0 ? 1 : 2;
+}
+
 // True when every lane of the wave holds centres in non-decreasing order.  A grid is, and a Lloyd
 // round keeps them so as long as every point goes to a centre of its own Voronoi cell; a point that
 // ties between two centres through rounding goes to the lower index and can pull that centre past
@@ -95,14 +204,14 @@ __device__ __forceinline__ void grid_centres(float lo, float hi, float (&c)[kK])
     for (int k = 0; k < kK; ++k) c[k] = __builtin_fmaf((float)k, step, lo);
 }
 
-// Lane-private accumulators: slot k * 64 + l belongs to cluster k of lane l.  Sums and counts both
-// sit in 8-byte slots, the counts 8 KB after the sums, so that one address serves both (the second
-// access is the same register plus a constant offset) and a wave's 64 slots of one access are
-// consecutive in LDS: the binary64 accesses then hit every bank evenly.  (Sum and count side by side
-// in one 16-byte record was measured with bank conflicts in 47 % of the LDS cycles.)
+// Lane-private accumulators: slot k * 64 + l belongs to cluster k of lane l, so a wave's 64 slots of one
+// access are consecutive in LDS and the binary64 accesses hit every bank evenly.  (Sum and count side by
+// side in one 16-byte record was measured with bank conflicts in 47 % of the LDS cycles.)  12 KiB per wave:
+// with 16 KiB (counts in 8-byte slots, which saved the shift in lloyd_add_at) a CU's 160 KiB of LDS held 10
+// waves where the registers allow 12.
 struct LloydScratch {
     double sum[kK * 64];
-    uint2 cnt[kK * 64];
+    uint32_t cnt[kK * 64];
 };
 
 __device__ __forceinline__ void lloyd_clear(LloydScratch& s, int lane)
@@ -110,7 +219,7 @@ __device__ __forceinline__ void lloyd_clear(LloydScratch& s, int lane)
 #pragma unroll
     for (int k = 0; k < kK; ++k) {
         s.sum[k * 64 + lane] = 0.0;
-        s.cnt[k * 64 + lane].x = 0u;
+        s.cnt[k * 64 + lane] = 0u;
     }
 }
 
@@ -121,36 +230,55 @@ __device__ __forceinline__ void lloyd_add(LloydScratch& s, int lane, int a, floa
 {
     const int slot = a * 64 + lane;
     __hip_atomic_fetch_add(&s.sum[slot], (double)x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
-    __hip_atomic_fetch_add(&s.cnt[slot].x, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+    __hip_atomic_fetch_add(&s.cnt[slot], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
 }
 
-// The same with the slot given as a byte offset: cluster * 512 | lane * 8 (sums and counts both have
-// 8-byte slots, so one offset serves both arrays).
+// Widening to binary64, pinned to where it is written.  The row's elements do not change between Lloyd
+// rounds, so the compiler would otherwise widen each of them once before the first round and keep the
+// results: two more registers per element for the whole kernel, which halves the number of waves a SIMD
+// can hold (or worse) to save one conversion per element and round (measured at dimension 64: 3.83 ms
+// with the widened copies kept, 2.80 ms without).
+__device__ __forceinline__ double widen_here(float x)
+{
+    double d;
+    asm volatile("v_cvt_f64_f32_e32 %0, %1" : "=v"(d) : "v"(x));
+    return d;
+}
+
+// The same with the slot given as the byte offset of its sum, cluster * 512 + lane * 8; the count sits at
+// half that offset in its own array.
 __device__ __forceinline__ void lloyd_add_at(LloydScratch& s, int byte_offset, float x)
 {
     double* sum = reinterpret_cast<double*>(reinterpret_cast<char*>(s.sum) + byte_offset);
-    uint32_t* cnt = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(s.cnt) + byte_offset);
-    __hip_atomic_fetch_add(sum, (double)x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
+    uint32_t* cnt = reinterpret_cast<uint32_t*>(reinterpret_cast<char*>(s.cnt) + (byte_offset >> 1));
+    __hip_atomic_fetch_add(sum, widen_here(x), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
     __hip_atomic_fetch_add(cnt, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WAVEFRONT);
 }
 
-// All 32 LDS reads are issued before the first division and the 16 divisions carry no branch, so
-// their dependent chains (about 15 binary64 instructions each) interleave instead of running one
-// after the other behind an LDS round trip each.
+// The means of one round, GROUP clusters at a time: the group's LDS reads are all issued before its
+// first division and the divisions carry no branch, so their dependent chains (about 15 binary64
+// instructions each) interleave instead of running one after the other behind an LDS round trip
+// each.  All 16 at once keeps 16 chains' temporaries alive on top of the row (more registers than
+// two waves per SIMD leave); groups of 8 interleave as well and need half of that.
+template <int GROUP = 8>
 __device__ __forceinline__ void lloyd_update(const LloydScratch& s, int lane, float (&c)[kK])
 {
-    uint32_t n[kK];
-    double sum[kK];
 #pragma unroll
-    for (int k = 0; k < kK; ++k) {
-        n[k] = s.cnt[k * 64 + lane].x;
-        sum[k] = s.sum[k * 64 + lane];
-    }
+    for (int g = 0; g < kK; g += GROUP) {
+        uint32_t n[GROUP];
+        double sum[GROUP];
 #pragma unroll
-    for (int k = 0; k < kK; ++k) {
-        float mean = (float)(sum[k] / (double)(n[k] > 0u ? n[k] : 1u));
-        asm volatile("" : "+v"(mean));  // keeps the division out of a per-cluster branch
-        c[k] = n[k] > 0u ? mean : c[k];
+        for (int k = 0; k < GROUP; ++k) {
+            n[k] = s.cnt[(g + k) * 64 + lane];
+            sum[k] = s.sum[(g + k) * 64 + lane];
+        }
+#pragma unroll
+        for (int k = 0; k < GROUP; ++k) {
+            float mean = (float)(sum[k] / (double)(n[k] > 0u ? n[k] : 1u));
+            asm volatile("" : "+v"(mean));  // keeps the division out of a per-cluster branch
+            c[g + k] = n[k] > 0u ? mean : c[g + k];
+        }
+        __builtin_amdgcn_sched_barrier(0);  // the next group's reads and divisions start after this group's
     }
 }
 
@@ -206,10 +334,27 @@ __device__ __forceinline__ void kmeans16_rpl_body(const KMeansArgs& a, int d, Ll
     }
     float c[kK];
     grid_centres(lo, hi, c);
+    const float min_gap = (hi - lo) * 0x1p-22f;  // see nearest_centre_separated
 
     for (int it = 0; it < a.lloyd_iters; ++it) {
         lloyd_clear(scratch, lane);
-        if (!a.force_scan && wave_centres_sorted(c)) {
+        const int order = a.force_scan ? 0 : wave_centre_order(c, min_gap);  // uniform over the wave
+        if (order == 2) {
+            constexpr int N = kSeparatedBatch;
+            static_assert(D % N == 0, "the batch divides the register row");
+#pragma unroll
+            for (int e = 0; e < D; e += N) {
+                float xs[N];
+                int slot[N];
+#pragma unroll
+                for (int i = 0; i < N; ++i) xs[i] = x[e + i];
+                nearest_centre_separated<512, N>(xs, c, lane * 8, lane * 8 + 8 * 512, slot);
+#pragma unroll
+                for (int i = 0; i < N; ++i)  // element order, as the sums require
+                    if (!TAIL || e + i < D - 7 || e + i < d) lloyd_add_at(scratch, slot[i], xs[i]);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        } else if (order == 1) {
 #pragma unroll
             for (int e = 0; e < D; ++e)
                 if (!TAIL || e < D - 7 || e < d) lloyd_add_at(scratch, nearest_centre_sorted<512>(x[e], c) | (lane * 8), x[e]);
@@ -230,7 +375,8 @@ __device__ __forceinline__ void kmeans16_rpl_body(const KMeansArgs& a, int d, Ll
     uint32_t w[NWORDS];
 #pragma unroll
     for (int k = 0; k < kK; ++k) ch[k] = through_f16(c[k]);
-    if (a.force_scan || !wave_centres_sorted(ch)) {
+    const int final_order = a.force_scan ? 0 : wave_centre_order(ch, min_gap);
+    if (final_order == 0) {
         if (live) {
             store_codebook(c, a.centroids_f16 + row * kK);
             uint8_t* out = a.idx + row * nbytes;
@@ -249,7 +395,8 @@ __device__ __forceinline__ void kmeans16_rpl_body(const KMeansArgs& a, int d, Ll
 #pragma unroll
         for (int e = 0; e < 8; ++e)
             if (8 * i + e < D) {
-                const uint32_t q = (uint32_t)nearest_centre_sorted(x[8 * i + e], ch);
+                const uint32_t q = (uint32_t)(final_order == 2 ? nearest_centre_separated(x[8 * i + e], ch)
+                                                               : nearest_centre_sorted(x[8 * i + e], ch));
                 acc |= ((!TAIL || 8 * i + e < D - 7 || 8 * i + e < d) ? q : 0u) << (4 * e);
             }
         w[i] = acc;

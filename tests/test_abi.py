@@ -32,7 +32,8 @@ def test_header_declares_the_expected_entry_points():
     for must in ["e4q_quantize_rowwise_greedy", "e4q_dequantize", "e4q_quantize_rowwise_greedy_batch",
                  "e4q_greedy_iterations", "e4q_strerror", "e4q_last_hip_error", "e4q_version",
                  "e4q_quantize_rowwise_kmeans16", "e4q_dequantize_codebook", "e4q_sparse_lengths_sum", "e4q_fuse_rows",
-                 "e4q_sparse_lengths_sum_fused", "e4q_fused_row_bytes", "e4q_set_option", "e4q_get_option"]:
+                 "e4q_sparse_lengths_sum_fused", "e4q_fused_row_bytes", "e4q_set_option", "e4q_get_option",
+                 "e4q_greedy_layout_cost"]:
         assert must in names
 
 
@@ -192,6 +193,12 @@ def test_diagnostic_options(lib):
         assert lib.e4q_quantize_rowwise_greedy_batch(descs, 2, 4, 100, 0.16, None) == -8
     finally:
         assert lib.e4q_set_option(b"greedy_layout", 0) == 0
+    lib.e4q_greedy_layout_cost.argtypes = [ctypes.c_int64, ctypes.c_int32, ctypes.c_int32, ctypes.c_int64]
+    lib.e4q_greedy_layout_cost.restype = ctypes.c_double
+    cost = lib.e4q_greedy_layout_cost
+    assert cost(10_000_000, 128, 32, 1) > 0 and cost(10_000_000, 128, 32, (8 << 8) | 16) > cost(10_000_000, 128, 32, 1)
+    assert cost(20_000, 128, 32, (16 << 8) | 8) < cost(20_000, 128, 32, 1)       # few rows: spread them over lanes
+    assert cost(1000, 256, 32, 1) < 0 and cost(1000, 256, 32, (8 << 8) | 4) < 0 and cost(1000, 64, 32, 0) < 0
     assert lib.e4q_set_option(b"kmeans_force_scan", 1) == 0 and lib.e4q_get_option(b"kmeans_force_scan") == 1
     assert lib.e4q_set_option(b"kmeans_force_scan", 0) == 0
 

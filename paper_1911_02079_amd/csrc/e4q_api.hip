@@ -159,9 +159,15 @@ int enqueue_greedy(const void* table, int dtype, int64_t rows, int32_t dim, int6
         while (E * L < dim) L *= 2;
     g_greedy_layout_chosen.store(E == 0 ? 1 : ((int64_t)E << 8) | L, std::memory_order_relaxed);
     hipError_t err;
-    if (E == 0 && dim % 8 == 0) {
+    if (E == 0 && dim % 8 == 0 && dim > 128) {
+        err = dtype == E4Q_F32 ? e4q::launch_greedy_rpl_wide_f32(a, dim, stream)
+                               : e4q::launch_greedy_rpl_wide_f16(a, dim, stream);
+    } else if (E == 0 && dim % 8 == 0) {
         err = dtype == E4Q_F32 ? e4q::launch_greedy_rpl_f32(a, dim, stream)
                                : e4q::launch_greedy_rpl_f16(a, dim, stream);
+    } else if (E == 0 && dim > 128) {
+        err = dtype == E4Q_F32 ? e4q::launch_greedy_rpl_wide_tail_f32(a, dim, stream)
+                               : e4q::launch_greedy_rpl_wide_tail_f16(a, dim, stream);
     } else if (E == 0) {
         err = dtype == E4Q_F32 ? e4q::launch_greedy_rpl_tail_f32(a, dim, stream)
                                : e4q::launch_greedy_rpl_tail_f16(a, dim, stream);
@@ -231,7 +237,7 @@ int e4q_quantize_rowwise_greedy_batch(const e4q_table_desc* descs, int32_t n_tab
     // one-row-per-lane kernels, go out in grouped launches of up to kMaxGroupTables tables.
     if (n_iter > 0 && g_greedy_layout.load(std::memory_order_relaxed) == 0) {
         for (int32_t t = 0; t < n_tables; ++t) {
-            if (done[t] || descs[t].rows == 0 || !e4q::rpl_supports_dim(descs[t].dim)) continue;
+            if (done[t] || descs[t].rows == 0 || !e4q::rpl_group_supports_dim(descs[t].dim)) continue;
             std::vector<int32_t> members;
             int64_t waves = 0;
             for (int32_t u = t; u < n_tables; ++u)

@@ -44,14 +44,21 @@ struct GreedyGroup {
     GreedyTable tables[kMaxGroupTables];
 };
 
-// Register-resident kernels exist for these dimensions (multiples of 8 up to 128).
-inline bool rpl_supports_dim(int32_t dim) { return dim >= 8 && dim <= 128 && dim % 8 == 0; }
-// Row per lane with a masked tail: any other dimension below 128 (registers for the next multiple of 8).
-inline bool rpl_tail_supports_dim(int32_t dim) { return dim >= 1 && dim < 128 && dim % 8 != 0; }
+// Register-resident kernels exist for these dimensions: multiples of 8 up to 224 (the row and some thirty
+// registers of working state must leave room for two waves per SIMD: 256 registers each).
+inline bool rpl_supports_dim(int32_t dim) { return dim >= 8 && dim <= 224 && dim % 8 == 0; }
+// The grouped (batch) launches are instantiated up to 128.
+inline bool rpl_group_supports_dim(int32_t dim) { return dim >= 8 && dim <= 128 && dim % 8 == 0; }
+// Row per lane with a masked tail: any other dimension below 224 (registers for the next multiple of 8).
+inline bool rpl_tail_supports_dim(int32_t dim) { return dim >= 1 && dim < 224 && dim % 8 != 0; }
 
 // Each returns hipGetLastError() after enqueueing.
 hipError_t launch_greedy_rpl_f32(const GreedyArgs& a, int32_t dim, hipStream_t stream);
 hipError_t launch_greedy_rpl_f16(const GreedyArgs& a, int32_t dim, hipStream_t stream);
+hipError_t launch_greedy_rpl_wide_f32(const GreedyArgs& a, int32_t dim, hipStream_t stream);  // 136 .. 224
+hipError_t launch_greedy_rpl_wide_f16(const GreedyArgs& a, int32_t dim, hipStream_t stream);
+hipError_t launch_greedy_rpl_wide_tail_f32(const GreedyArgs& a, int32_t dim, hipStream_t stream);  // 129 .. 223, not 8k
+hipError_t launch_greedy_rpl_wide_tail_f16(const GreedyArgs& a, int32_t dim, hipStream_t stream);
 hipError_t launch_greedy_rpl_tail_f32(const GreedyArgs& a, int32_t dim, hipStream_t stream);
 hipError_t launch_greedy_rpl_tail_f16(const GreedyArgs& a, int32_t dim, hipStream_t stream);
 hipError_t launch_greedy_rpl_group_f32(const GreedyGroup& g, int32_t dim, hipStream_t stream);

@@ -1,0 +1,9 @@
+// Row-per-lane greedy kernels for binary32 tables of dimension 136 .. 224.
+#include "greedy_rpl_inst.h"
+
+namespace e4q {
+hipError_t launch_greedy_rpl_wide_f32(const GreedyArgs& a, int32_t dim, hipStream_t stream)
+{
+    return dispatch_greedy_rpl_wide<float>(a, dim, stream);
+}
+}  // namespace e4q

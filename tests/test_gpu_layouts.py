@@ -31,7 +31,7 @@ def e4q():
 def layouts_for(dim):
     """One row per lane where it exists, then every compiled (E, L) with the smallest L that holds
     the row, plus one with twice that many lanes (lanes beyond the row hold no element)."""
-    out = ["rpl"] if dim <= 128 else []
+    out = ["rpl"] if dim <= 224 else []
     for e in (8, 16, 32, 64, 128):
         l = 1
         while e * l < dim:
@@ -45,7 +45,7 @@ def layouts_for(dim):
 
 
 @pytest.mark.parametrize("half", [False, True], ids=["f32", "f16"])
-@pytest.mark.parametrize("dim", [32, 64, 100, 128, 200, 1000])
+@pytest.mark.parametrize("dim", [32, 64, 100, 128, 136, 150, 192, 199, 200, 223, 224, 1000])
 def test_every_forced_layout_matches_the_oracle(e4q, oracle_lib, dim, half):
     from paper_1911_02079_amd import synth
 

@@ -482,6 +482,7 @@ def test_binding_reports_library_errors(e4q):
     (131, 2048, torch.float16, 0.16),                                  # few rows: 8..64 per lane
     (MANY, 100, torch.float32, 0.16), (MANY, 200, torch.float32, 0.16), (MANY, 256, torch.float16, 0.16),
     (MANY, 36, torch.float32, 0.16),                                   # many rows, long chunks, masked
+    (MANY, 150, torch.float32, 0.16), (MANY, 199, torch.float16, 0.16), (MANY, 224, torch.float32, 0.16),  # one row per lane above 128
     (50_001, 128, torch.float32, 0.0), (50_001, 24, torch.float32, 0.0), (50_001, 100, torch.float32, 0.0),
 ])
 def test_other_bit_widths(e4q, oracle_lib, nbits, rows, dim, dtype, ratio):
@@ -512,7 +513,7 @@ def test_other_bit_widths_batch_and_guard_bands(e4q, oracle_lib):
         for t, (codes, scale, bias) in zip(tables, outs):
             o = oracle_lib.quantize_rowwise_greedy(t.cpu().numpy(), 20, 0.25, nbits=nbits)
             assert np.array_equal(codes.cpu().numpy(), o[0]) and np.array_equal(f16_bits(scale), o[1])
-        for dim, rows in ((64, 64 * 512 + 5), (13, 197), (200, 64 * 512 + 5)):
+        for dim, rows in ((64, 64 * 512 + 5), (13, 197), (200, 64 * 512 + 5), (199, 64 * 512 + 5)):
             t = synth.gaussian_table(rows, dim, 0.1, seed=9, device="cuda")
             nb = e4q.packed_bytes(dim, nbits)
             cbuf = torch.full((rows * nb + 256,), 0xA5, dtype=torch.uint8, device="cuda")

@@ -215,7 +215,7 @@ int32_t e4q_greedy_iterations(int32_t n_bins, float ratio);
  * call or the next.  Host-only.
  *
  *   "greedy_layout"      0: the library picks the thread layout of the greedy search (default).
- *                        1: one table row per lane (dim <= 128 only).
+ *                        1: one table row per lane (dim <= 224 only).
  *                        (E << 8) | L: L lanes per row with E contiguous elements each,
  *                        E in {8, 16, 32, 64, 128}, L a power of two <= 64 (<= 32 for E = 128).
  *                        A forced layout needs E * L >= dim; the quantize calls return

@@ -182,12 +182,12 @@ def test_diagnostic_options(lib):
         assert lib.e4q_get_option(b"greedy_layout") == (8 << 8) | 4
         assert q(p, 0, 10, 64, 64, 4, 200, 0.16, p, p, p, None) == -8
         assert q(p, 0, 10, 64, 64, 3, 200, 0.16, p, p, p, None) == -3       # ordinary validation comes first
-        assert lib.e4q_set_option(b"greedy_layout", 1) == 0                  # one row per lane: dim <= 128
+        assert lib.e4q_set_option(b"greedy_layout", 1) == 0                  # one row per lane: dim <= 224
         assert q(p, 0, 10, 256, 256, 4, 200, 0.16, p, p, p, None) == -8
         from paper_1911_02079_amd.binding import TableDesc
 
         descs = (TableDesc * 2)()
-        for d, dim in zip(descs, (64, 200)):
+        for d, dim in zip(descs, (64, 256)):
             d.table, d.dtype, d.dim, d.rows, d.row_stride = 0x1000, 0, dim, 5, dim
             d.codes, d.scale_f16, d.bias_f16 = 0x1000, 0x1000, 0x1000
         assert lib.e4q_quantize_rowwise_greedy_batch(descs, 2, 4, 100, 0.16, None) == -8

@@ -122,7 +122,19 @@ __device__ __forceinline__ float tree_sum(Leaf&& leaf)
 // fill in (measured 4 % to 12 % over no hint; priorities inside a kernel only order waves of a SIMD).
 constexpr int kStage = 4;
 
-template <int LO, int SPAN, int D, bool MASKED, int VALID_BELOW = 0>
+// The mask of tree_sq_err when `nvalid` is the same for every lane (UNIFORM_MASK): a multiplication by 1.0f or
+// 0.0f held in a scalar register the optimizer cannot see through (a squared error is finite and not
+// negative, so the product is the term itself or +0.0f, what a select would give): a select on a
+// wave-uniform condition is turned into a branch around the element's arithmetic, and with a branch
+// in the block the rest of the arithmetic is moved behind it, out of the pinned order.
+__device__ __forceinline__ float uniform_keep_factor(bool exists)
+{
+    uint32_t m = exists ? 0x3f800000u : 0u;  // the bits of 1.0f or 0.0f, selected on the scalar unit
+    asm volatile("" : "+s"(m));
+    return __builtin_bit_cast(float, m);
+}
+
+template <int LO, int SPAN, int D, bool MASKED, int VALID_BELOW = 0, bool UNIFORM_MASK = false>
 __device__ __forceinline__ float tree_sq_err(const float (&x)[D], const StoredParams& p, int nvalid)
 {
     static_assert(LO < D, "empty subtree");
@@ -154,8 +166,12 @@ __device__ __forceinline__ float tree_sq_err(const float (&x)[D], const StoredPa
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (MASKED) {
 #pragma unroll
-            for (int i = 0; i < N; ++i)
-                if (LO + i >= VALID_BELOW) t[i] = (LO + i < nvalid) ? t[i] : 0.0f;
+            for (int i = 0; i < N; ++i) {
+                if (LO + i < VALID_BELOW) continue;
+                if constexpr (UNIFORM_MASK) t[i] = t[i] * uniform_keep_factor(LO + i < nvalid);
+                else t[i] = (LO + i < nvalid) ? t[i] : 0.0f;
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
         const float s = tree_sum<0, SPAN, N>([&](auto k) { return t[decltype(k)::value]; });
         __builtin_amdgcn_sched_barrier(0);
@@ -163,10 +179,10 @@ __device__ __forceinline__ float tree_sq_err(const float (&x)[D], const StoredPa
     } else {
         constexpr int H = SPAN / 2;
         if constexpr (LO + H >= D) {
-            return tree_sq_err<LO, H, D, MASKED, VALID_BELOW>(x, p, nvalid);  // right half is padding
+            return tree_sq_err<LO, H, D, MASKED, VALID_BELOW, UNIFORM_MASK>(x, p, nvalid);  // right half is padding
         } else {
-            const float a = tree_sq_err<LO, H, D, MASKED, VALID_BELOW>(x, p, nvalid);
-            const float b = tree_sq_err<LO + H, H, D, MASKED, VALID_BELOW>(x, p, nvalid);
+            const float a = tree_sq_err<LO, H, D, MASKED, VALID_BELOW, UNIFORM_MASK>(x, p, nvalid);
+            const float b = tree_sq_err<LO + H, H, D, MASKED, VALID_BELOW, UNIFORM_MASK>(x, p, nvalid);
             return a + b;
         }
     }

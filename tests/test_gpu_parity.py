@@ -324,7 +324,7 @@ def test_strided_and_unaligned_views(e4q, oracle_lib):
 
 
 @pytest.mark.parametrize("nbits", [2, 4, 8])
-@pytest.mark.parametrize("dim", [1, 3, 7, 13, 50, 101, 127, 130])
+@pytest.mark.parametrize("dim", [1, 3, 4, 5, 6, 7, 13, 50, 101, 127, 130])
 def test_dequantize_odd_dimensions_aligned_and_not(e4q, oracle_lib, dim, nbits):
     """dim % 4 != 0: four flattened elements per thread into a 16-byte aligned output (groups straddle row
     boundaries, the last group is partial), one element per thread into an output that is not; and an odd

@@ -209,6 +209,11 @@ static greedy_result greedy_row(const float *x, int d, int32_t n_bins, int32_t n
         if (x[k] < lo0) lo0 = x[k];
         if (x[k] > hi0) hi0 = x[k];
     }
+    /* -0 and +0 are the same number, so "min X" and "max X" (Algorithm 1, lines 1-2) do not say which
+       one a zero bound is when a row holds both: a zero bound is taken as +0 (adding +0 does that and
+       changes nothing else). */
+    lo0 = lo0 + 0.0f;
+    hi0 = hi0 + 0.0f;
     greedy_result best = {lo0, hi0, 0.0f, 0, 0};
     if (hi0 == lo0) /* constant row: stepsize is 0 and the loop of Algorithm 1 never runs */
         return best;
@@ -344,6 +349,8 @@ int e4q_oracle_brute_force_row(const float *x, int32_t dim, int32_t n_bins, int3
         if (x[k] < lo0) lo0 = x[k];
         if (x[k] > hi0) hi0 = x[k];
     }
+    lo0 = lo0 + 0.0f; /* a zero bound is +0, as in greedy_row */
+    hi0 = hi0 + 0.0f;
     float stepsize = (hi0 - lo0) / (float)n_bins;
     float bl = INFINITY;
     int32_t bi = 0, bj = 0;

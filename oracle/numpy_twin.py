@@ -56,7 +56,7 @@ def loss(x: np.ndarray, lo: F32, hi: F32, qmax: float = 15.0) -> F32:
 
 def greedy_row(x: np.ndarray, n_bins: int, ratio: float, literal_alg1: bool = False, qmax: float = 15.0):
     x = x.astype(F32)
-    lo0, hi0 = F32(x.min()), F32(x.max())
+    lo0, hi0 = F32(x.min()) + F32(0), F32(x.max()) + F32(0)   # a zero bound is +0 whichever zeros the row holds
     if lo0 == hi0:
         return lo0, hi0, F32(0), 0, 0
     br = float(n_bins) * float(F32(ratio))

@@ -46,6 +46,9 @@ __device__ __forceinline__ float f16_bits_to_float(uint16_t b)
     return opaque((float)__builtin_bit_cast(_Float16, b));
 }
 
+// -0 becomes +0, every other value stays (round-to-nearest: -0 + +0 = +0).
+__device__ __forceinline__ float canonical_zero(float v) { return v + 0.0f; }
+
 // The parameters that are stored for the clipping range [lo, hi] (Eq. 1 with binary16 storage):
 // scale = (hi - lo)/(2^n - 1) and bias = lo, both rounded to binary16, the reciprocal used by the
 // quantizer (0 when the range collapses, which sends every code to 0), and the largest code.

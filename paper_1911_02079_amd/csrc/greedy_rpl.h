@@ -105,6 +105,10 @@ __device__ __forceinline__ void greedy_rpl_row(const GreedyArgs& a, int64_t row,
         lo0 = __builtin_fminf(lo0, x[k]);
         hi0 = __builtin_fmaxf(hi0, x[k]);
     }
+    // A row may hold zeros of both signs; which of them a zero bound is depends on the order of the
+    // comparisons.  Zero bounds are +0 by definition (the stored bias would differ in its sign bit).
+    lo0 = canonical_zero(lo0);
+    hi0 = canonical_zero(hi0);
 
     float best_lo = lo0, best_hi = hi0;
     if (a.n_iter > 0) {  // uniform branch: ratio == 0 needs no scoring at all

@@ -129,6 +129,8 @@ __global__ void __launch_bounds__(kSwlBlock) greedy_swl_kernel(GreedyArgs a, int
     }
     lo0 = group_reduce<L>(lo0, [](float p, float q) { return __builtin_fminf(p, q); });
     hi0 = group_reduce<L>(hi0, [](float p, float q) { return __builtin_fmaxf(p, q); });
+    lo0 = canonical_zero(lo0);  // zero bounds are +0 whichever zeros the row holds
+    hi0 = canonical_zero(hi0);
 
     float best_lo = lo0, best_hi = hi0;
     if (a.n_iter > 0) {

@@ -420,6 +420,63 @@ def test_random_shapes(e4q, oracle_lib, rows, dim, half, nbits, n_bins, ratio):
     assert np.array_equal(xh.cpu().numpy(), oracle_lib.dequantize(o[0], o[1], o[2], dim, nbits=nbits))
 
 
+@pytest.mark.parametrize("nbits", [2, 4, 8])
+@pytest.mark.parametrize("dim,half", [(8, False), (24, False), (64, True), (100, False), (136, False), (320, False)])
+def test_every_binade_of_scale(e4q, oracle_lib, dim, half, nbits):
+    """Rows scaled by 2^-22 ... 2^13: the stored scale runs through the binary16 subnormals and every normal
+    binade, so the per-range divisions (range / (2^n - 1) and 1 / scale, which the kernels take by a short
+    sequence) are compared with the oracle's plain divisions across their whole working range."""
+    from helpers import oracle_rows_in_parallel
+    from paper_1911_02079_amd import synth
+
+    rows = 36 * 64 * 3 + 11
+    t = synth.outlier_table(rows, dim, seed=4242 + dim + nbits, device="cuda")
+    t = t / t.abs().amax(dim=1, keepdim=True)                                  # every row within [-1, 1]
+    k = (torch.arange(rows, device="cuda") % 36 - 22).to(torch.float32)         # -22 ... 13
+    t = t * torch.exp2(k)[:, None] * torch.linspace(1.0, 1.99, rows, device="cuda")[:, None]
+    if half:
+        t = t.half()
+    say(f"every binade dim={dim} half={half} nbits={nbits}")
+    codes, scale, bias = e4q.quantize_rowwise_greedy(t, 40, 0.3, nbits=nbits)
+    torch.cuda.synchronize()
+    o = oracle_rows_in_parallel(oracle_lib, t.cpu().numpy(), 40, 0.3, nbits=nbits)
+    bad = np.flatnonzero((codes.cpu().numpy() != o[0]).any(axis=1) | (f16_bits(scale) != o[1]) | (f16_bits(bias) != o[2]))
+    assert bad.size == 0, f"{bad.size} rows differ, first {bad[:5]}"
+    assert len(np.unique(o[1] >> 10)) >= 20   # the stored scales do span the binary16 exponents, subnormals included
+
+
+@pytest.mark.parametrize("dim,half", [(8, False), (64, True), (100, False), (128, False), (200, False), (512, True)])
+def test_rows_with_zeros_of_both_signs(e4q, oracle_lib, dim, half):
+    """Sparse rows whose zeros carry either sign (what pruning or a binary16 conversion of tiny negative
+    values leaves behind), rows of zeros only, rows whose maximum is zero: a zero bound is +0 on both
+    sides, so the stored bias and scale bits agree whatever order the kernel compares the elements in."""
+    from helpers import oracle_rows_in_parallel
+    from paper_1911_02079_amd import synth
+
+    rows = 64 * 21 + 13
+    g = torch.Generator(device="cuda").manual_seed(9100 + dim)
+    t = synth.gaussian_table(rows, dim, 0.1, seed=9000 + dim, device="cuda")
+    keep = torch.rand((rows, dim), device="cuda", generator=g) < 0.3
+    negzero = torch.rand((rows, dim), device="cuda", generator=g) < 0.5
+    t = torch.where(keep, t, torch.where(negzero, torch.full_like(t, -0.0), torch.zeros_like(t)))
+    t[1::7] = t[1::7].abs()            # minimum zero
+    t[2::7] = -t[2::7].abs()           # maximum zero
+    t[3::7] = torch.where(negzero[3::7], torch.full_like(t[3::7], -0.0), torch.zeros_like(t[3::7]))  # zeros only
+    t[4::49] = -0.0                    # nothing but -0
+    if half:
+        t = t.half()
+    say(f"signed zeros dim={dim} half={half}")
+    for ratio in (0.0, 0.25):
+        codes, scale, bias = e4q.quantize_rowwise_greedy(t, 30, ratio)
+        xh = e4q.dequantize(codes, scale, bias, dim)
+        torch.cuda.synchronize()
+        o = oracle_rows_in_parallel(oracle_lib, t.cpu().numpy(), 30, ratio)
+        bad = np.flatnonzero((codes.cpu().numpy() != o[0]).any(axis=1) | (f16_bits(scale) != o[1]) | (f16_bits(bias) != o[2]))
+        assert bad.size == 0, f"ratio {ratio}: {bad.size} rows differ, first {bad[:5]}"
+        want = oracle_lib.dequantize(o[0], o[1], o[2], dim)
+        assert np.array_equal(xh.cpu().numpy().view(np.uint32), want.view(np.uint32))   # signs of zeros included
+
+
 def test_outputs_do_not_overrun(e4q):
     """Guard bands around the outputs stay untouched (ragged row count, fast and fallback paths)."""
     from paper_1911_02079_amd import synth

@@ -71,6 +71,7 @@ MUTANTS = {
                                        "for (int k = 0; k < d; ++k) dst[k] = (float)src[k];"),
     "binary16_rows_at_binary32_pitch": ("const uint16_t *src = (const uint16_t *)table + row * row_stride;",
                                         "const uint16_t *src = (const uint16_t *)table + 2 * row * row_stride;"),
+    "zero_minimum_keeps_its_sign": ("    lo0 = lo0 + 0.0f;\n    hi0 = hi0 + 0.0f;\n    greedy_result best", "    greedy_result best"),
 }
 
 

@@ -337,6 +337,32 @@ def test_constant_and_tiny_range_rows(oracle_lib):
     assert np.array_equal(oracle_lib.dequantize(codes, sc, bi, 10)[:3], table[:3])
 
 
+def test_zero_bounds_are_positive_zero(oracle_lib):
+    """-0 = +0, so "min X" does not say which zero a zero minimum is when a row holds both (Algorithm 1,
+    lines 1-2, is silent): a zero bound is +0, wherever the zeros stand in the row.  Pinned on the stored
+    bits: bias 0x0000, never 0x8000, and scale +0 for rows of nothing but zeros; the codes and the
+    de-quantized values do not depend on the order of the zeros either."""
+    nz, pz = np.float32(-0.0), np.float32(0.0)
+    rows = np.array([
+        [nz, pz, 1.0, 0.5, pz, nz, 0.25, 1.0],      # minimum zero, -0 first
+        [pz, nz, 1.0, 0.5, nz, pz, 0.25, 1.0],      # the same numbers, +0 first
+        [nz, nz, nz, nz, nz, nz, nz, nz],           # nothing but -0
+        [nz, pz, nz, pz, nz, pz, nz, pz],           # zeros of both signs only
+        [-1.0, nz, pz, -0.5, nz, -0.25, pz, -1.0],  # maximum zero
+        [-1.0, pz, nz, -0.5, pz, -0.25, nz, -1.0],
+    ], dtype=np.float32)
+    for ratio in (0.0, 0.3):
+        codes, sc, bi = oracle_lib.quantize_rowwise_greedy(rows, 20, ratio)[:3]
+        assert np.array_equal(bi[:4], [0, 0, 0, 0])
+        assert np.array_equal(sc[2:4], [0, 0])
+        assert np.array_equal(codes[0], codes[1]) and sc[0] == sc[1]
+        assert np.array_equal(codes[4], codes[5]) and sc[4] == sc[5] and bi[4] == bi[5]
+        assert np.all(codes[2:4] == 0)
+        xh = oracle_lib.dequantize(codes, sc, bi, 8)
+        assert np.array_equal(xh[0], xh[1]) and np.array_equal(xh[4], xh[5])
+        assert not np.signbit(xh[2:4]).any()
+
+
 def test_summation_is_the_adjacent_pair_tree(oracle_lib):
     """Squared errors are summed by a balanced tree over index-adjacent pairs.  Built so that
     errors are known integers with squares near 2^24: then other orders (left to right,

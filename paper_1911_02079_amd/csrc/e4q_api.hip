@@ -80,8 +80,8 @@ int validate_forced_layout(int32_t dim)
 }
 
 // Estimated duration of the greedy search, in SIMD cycles, for `rows` rows with `elems` elements per
-// lane and `lanes` lanes per row.  Instructions per wave and scored range: 8 per element, about 48 of
-// per-range scalar work (two divisions, two binary16 round trips, the decisions) and 6 per butterfly
+// lane and `lanes` lanes per row.  Instructions per wave and scored range: 8 per element, about 30 of
+// per-range scalar work (two short divisions, two binary16 round trips, the decisions) and 6 per butterfly
 // step.  Cycles per instruction as measured on gfx950: a SIMD with one or two waves issues one
 // instruction per wave every 5.2 cycles (so two waves cost what one costs), three waves 8.3 in total,
 // four or more 2.45 each.  Fitted on 20 k - 1 M rows at dim 32 / 64 / 128; within 10 % of the
@@ -90,7 +90,7 @@ double layout_cost(int64_t rows, int32_t elems, int32_t lanes, int32_t n_iter, b
 {
     int steps = 0;
     while ((1 << steps) < lanes) ++steps;
-    const double per_range = 8.0 * elems + 48.0 + 6.0 * steps;
+    const double per_range = 8.0 * elems + 30.0 + 6.0 * steps;
     const double instructions = (1.0 + 2.0 * n_iter) * per_range + 10.0 * elems;
     const int64_t rows_per_block = row_per_lane ? 64 : 256 / lanes;
     const int64_t waves = (rows + rows_per_block - 1) / rows_per_block * (row_per_lane ? 1 : 4);

@@ -162,8 +162,19 @@ __device__ __forceinline__ float uniform_keep_factor(bool exists)
     return __builtin_bit_cast(float, m);
 }
 
+// With a mask that differs between lanes (MASKED without UNIFORM_MASK) the caller passes `keep`, one factor per
+// element, 1.0f where the element exists and 0.0f where it does not, made once per row and hidden from the
+// optimizer in the same way (lane_keep_factor); otherwise `keep` is not read.
+__device__ __forceinline__ float lane_keep_factor(bool exists)
+{
+    float m = exists ? 1.0f : 0.0f;
+    asm("" : "+v"(m));
+    return m;
+}
+
 template <int LO, int SPAN, int D, bool MASKED, int VALID_BELOW = 0, bool UNIFORM_MASK = false>
-__device__ __forceinline__ float tree_sq_err(const float (&x)[D], const StoredParams& p, int nvalid)
+__device__ __forceinline__ float tree_sq_err(const float (&x)[D], const StoredParams& p, int nvalid,
+                                             const float (&keep)[D])
 {
     static_assert(LO < D, "empty subtree");
     if constexpr (SPAN <= kStage) {
@@ -197,7 +208,7 @@ __device__ __forceinline__ float tree_sq_err(const float (&x)[D], const StoredPa
             for (int i = 0; i < N; ++i) {
                 if (LO + i < VALID_BELOW) continue;
                 if constexpr (UNIFORM_MASK) t[i] = t[i] * uniform_keep_factor(LO + i < nvalid);
-                else t[i] = (LO + i < nvalid) ? t[i] : 0.0f;
+                else t[i] = t[i] * keep[LO + i];
             }
             __builtin_amdgcn_sched_barrier(0);
         }
@@ -207,10 +218,10 @@ __device__ __forceinline__ float tree_sq_err(const float (&x)[D], const StoredPa
     } else {
         constexpr int H = SPAN / 2;
         if constexpr (LO + H >= D) {
-            return tree_sq_err<LO, H, D, MASKED, VALID_BELOW, UNIFORM_MASK>(x, p, nvalid);  // right half is padding
+            return tree_sq_err<LO, H, D, MASKED, VALID_BELOW, UNIFORM_MASK>(x, p, nvalid, keep);  // right half is padding
         } else {
-            const float a = tree_sq_err<LO, H, D, MASKED, VALID_BELOW, UNIFORM_MASK>(x, p, nvalid);
-            const float b = tree_sq_err<LO + H, H, D, MASKED, VALID_BELOW, UNIFORM_MASK>(x, p, nvalid);
+            const float a = tree_sq_err<LO, H, D, MASKED, VALID_BELOW, UNIFORM_MASK>(x, p, nvalid, keep);
+            const float b = tree_sq_err<LO + H, H, D, MASKED, VALID_BELOW, UNIFORM_MASK>(x, p, nvalid, keep);
             return a + b;
         }
     }

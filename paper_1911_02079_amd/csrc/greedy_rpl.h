@@ -69,7 +69,7 @@ template <int D, bool TAIL>
 __device__ __forceinline__ float range_loss(const float (&x)[D], float lo, float hi, float qmax, int d)
 {
     const StoredParams p = stored_params(lo, hi, qmax);
-    return tree_sq_err<0, next_pow2(D), D, TAIL, D - 7, true>(x, p, d);
+    return tree_sq_err<0, next_pow2(D), D, TAIL, D - 7, true>(x, p, d, x);  // uniform mask: no factors
 }
 
 // The whole path for the row this lane owns: load, min/max, Algorithm 1, encode, store.

@@ -66,7 +66,8 @@ __device__ __forceinline__ float group_reduce(float v, Op op)
 }
 
 template <int E, int L, int MASK>
-__device__ __forceinline__ float swl_range_loss(const float (&x)[E], int nvalid, float lo, float hi, float qmax)
+__device__ __forceinline__ float swl_range_loss(const float (&x)[E], const float (&keep)[E], int nvalid, float lo,
+                                                float hi, float qmax)
 {
     const StoredParams p = stored_params(lo, hi, qmax);
     float part;
@@ -75,11 +76,11 @@ __device__ __forceinline__ float swl_range_loss(const float (&x)[E], int nvalid,
         const int nblocks = nvalid / 8;
         part = tree_sum<0, E / 8, E / 8>([&](auto b) {
             constexpr int blk = decltype(b)::value;
-            const float bs = tree_sq_err<8 * blk, 8, E, false>(x, p, E);
+            const float bs = tree_sq_err<8 * blk, 8, E, false>(x, p, E, keep);
             return (blk < nblocks) ? bs : 0.0f;
         });
     } else {
-        part = tree_sq_err<0, E, E, MASK == 2>(x, p, nvalid);
+        part = tree_sq_err<0, E, E, MASK == 2>(x, p, nvalid, keep);
     }
     return group_reduce<L>(part, [](float a, float b) { return a + b; });
 }
@@ -132,16 +133,23 @@ __global__ void __launch_bounds__(kSwlBlock) greedy_swl_kernel(GreedyArgs a, int
     lo0 = canonical_zero(lo0);  // zero bounds are +0 whichever zeros the row holds
     hi0 = canonical_zero(hi0);
 
+    // MASK = 2: one factor per element, 1.0f if it exists in this lane's part of the row (see tree_sq_err)
+    float keep[E];
+    if constexpr (MASK == 2) {
+#pragma unroll
+        for (int e = 0; e < E; ++e) keep[e] = lane_keep_factor(e < nvalid);
+    }
+
     float best_lo = lo0, best_hi = hi0;
     if (a.n_iter > 0) {
         const float stepsize = (hi0 - lo0) / a.n_bins;
         float cur_lo = lo0, cur_hi = hi0;
-        float best = swl_range_loss<E, L, MASK>(x, nvalid, lo0, hi0, a.qmax);
+        float best = swl_range_loss<E, L, MASK>(x, keep, nvalid, lo0, hi0, a.qmax);
         for (int it = 0; it < a.n_iter; ++it) {
             const float next_lo = cur_lo + stepsize;
             const float next_hi = cur_hi - stepsize;
-            const float loss_l = swl_range_loss<E, L, MASK>(x, nvalid, next_lo, cur_hi, a.qmax);
-            const float loss_r = swl_range_loss<E, L, MASK>(x, nvalid, cur_lo, next_hi, a.qmax);
+            const float loss_l = swl_range_loss<E, L, MASK>(x, keep, nvalid, next_lo, cur_hi, a.qmax);
+            const float loss_r = swl_range_loss<E, L, MASK>(x, keep, nvalid, cur_lo, next_hi, a.qmax);
             const bool left = loss_l < loss_r;  // a tie moves the upper bound
             cur_lo = left ? next_lo : cur_lo;
             cur_hi = left ? cur_hi : next_hi;

@@ -217,7 +217,8 @@ int32_t e4q_greedy_iterations(int32_t n_bins, float ratio);
  *   "greedy_layout"      0: the library picks the thread layout of the greedy search (default).
  *                        1: one table row per lane (dim <= 224 only).
  *                        (E << 8) | L: L lanes per row with E contiguous elements each,
- *                        E in {8, 16, 32, 64, 128}, L a power of two <= 64 (<= 32 for E = 128).
+ *                        E in {8, 16, 32, 64, 128}, 1 <= L <= 64 (not 64 for E = 128); an L that is not a
+ *                        power of two leaves 64 % L lanes of every wave idle.
  *                        A forced layout needs E * L >= dim; the quantize calls return
  *                        E4Q_ERR_BAD_OPTION otherwise.  The batch call then launches table by table.
  *   "kmeans_force_scan"  1: e4q_quantize_rowwise_kmeans16 scans all 16 centres for every value

@@ -21,7 +21,7 @@ LIB_PATH = os.path.join(HERE, "libe4q.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 SOURCES = ["e4q_api.hip", "greedy_rpl_f32.hip", "greedy_rpl_f16.hip", "greedy_rpl_tail_f32.hip", "greedy_rpl_tail_f16.hip", "greedy_rpl_wide_f32.hip", "greedy_rpl_wide_f16.hip", "greedy_rpl_wide_tail_f32.hip", "greedy_rpl_wide_tail_f16.hip", "greedy_swl_f32_small.hip", "greedy_swl_f32_mid.hip",
-           "greedy_swl_f32_big.hip", "greedy_swl_f16_small.hip", "greedy_swl_f16_mid.hip", "greedy_swl_f16_big.hip", "dequantize.hip", "kmeans16_f32.hip",
+           "greedy_swl_f32_big.hip", "greedy_swl_f16_small.hip", "greedy_swl_f16_mid.hip", "greedy_swl_f16_big.hip", "greedy_swl_any_f32.hip", "greedy_swl_any_f16.hip", "dequantize.hip", "kmeans16_f32.hip",
            "kmeans16_f16.hip", "kmeans16_tail_f32.hip", "kmeans16_tail_f16.hip", "kmeans16_misc.hip", "sls.hip"]
 
 FLAGS = [

@@ -43,7 +43,8 @@ bool layout_value_ok(int64_t v)
     if (v == 0 || v == 1) return true;
     const int64_t e = v >> 8, l = v & 0xff;
     if (e != 8 && e != 16 && e != 32 && e != 64 && e != 128) return false;
-    if (l < 1 || l > (e == 128 ? 32 : 64) || (l & (l - 1)) != 0) return false;
+    if (l < 1 || l > 64) return false;
+    if ((l & (l - 1)) == 0 && e == 128 && l > 32) return false;  // not instantiated: dim <= 4096
     return true;
 }
 
@@ -90,9 +91,12 @@ double layout_cost(int64_t rows, int32_t elems, int32_t lanes, int32_t n_iter, b
 {
     int steps = 0;
     while ((1 << steps) < lanes) ++steps;
-    const double per_range = 8.0 * elems + 30.0 + 6.0 * steps;
+    // a lane count that is not a power of two sums across lanes by ds_bpermute (one per step and one to hand
+    // the result round, each worth some 14 instructions with its select and addition) instead of DPP moves
+    const bool pow2 = (lanes & (lanes - 1)) == 0;
+    const double per_range = 8.0 * elems + 30.0 + (pow2 ? 6.0 * steps : 14.0 * (steps + 1));
     const double instructions = (1.0 + 2.0 * n_iter) * per_range + 10.0 * elems;
-    const int64_t rows_per_block = row_per_lane ? 64 : 256 / lanes;
+    const int64_t rows_per_block = row_per_lane ? 64 : 4 * (64 / lanes);
     const int64_t waves = (rows + rows_per_block - 1) / rows_per_block * (row_per_lane ? 1 : 4);
     const int64_t per_simd = (waves + 1023) / 1024;
     const double cycles_per_instruction = per_simd <= 2 ? 5.2 : per_simd == 3 ? 8.3 : 2.45 * (double)per_simd;
@@ -135,28 +139,30 @@ int enqueue_greedy(const void* table, int dtype, int64_t rows, int32_t dim, int6
         if ((int64_t)E * L < dim) return E4Q_ERR_BAD_OPTION;
     } else if (n_iter == 0) {
         E = dim <= 512 ? 8 : dim <= 1024 ? 16 : dim <= 2048 ? 32 : 64;
+        while (E * L < dim) L *= 2;
     } else {
         const bool rpl = e4q::rpl_supports_dim(dim) || e4q::rpl_tail_supports_dim(dim);
         double best = rpl ? layout_cost(rows, (dim + 7) / 8 * 8, 1, n_iter, true) : -1.0;
-        // A dimension that is not a multiple of 8 carries one validity mask per element; 32 of them
-        // are what the scalar registers hold without spilling (measured: dim 100 takes 2.7 ms per
-        // 2 M rows with E = 32, 6.0 ms with E = 128).
+        // A dimension that is not a multiple of 8 carries one mask factor per element in a register of
+        // its own: with 32 elements per lane five waves per SIMD still fit, with 64 three, with 128 one.
         const int e_max = dim % 8 == 0 ? 128 : (dim <= 2048 ? 32 : 64);
         for (int e = 8; e <= e_max; e *= 2) {
             if (e > 8 && e / 2 >= dim) break;  // more than half of every lane would be padding
-            int l = 1;
-            while (e * l < dim) l *= 2;
-            if (l > (e == 128 ? 32 : 64)) continue;
-            const double c = layout_cost(rows, e, l, n_iter, false);
-            if (best < 0.0 || c < best) {
-                best = c;
-                E = e;
-                L = l;
+            // the fewest lanes that hold the row, and the next power of two (sums by DPP moves)
+            const int l_min = (dim + e - 1) / e;
+            int l_pow2 = 1;
+            while (l_pow2 < l_min) l_pow2 *= 2;
+            for (int l : {l_min, l_pow2}) {
+                if (l > 64) continue;
+                const double c = layout_cost(rows, e, l, n_iter, false);
+                if (best < 0.0 || c < best) {
+                    best = c;
+                    E = e;
+                    L = l;
+                }
             }
         }
     }
-    if (E != 0)
-        while (E * L < dim) L *= 2;
     g_greedy_layout_chosen.store(E == 0 ? 1 : ((int64_t)E << 8) | L, std::memory_order_relaxed);
     hipError_t err;
     if (E == 0 && dim % 8 == 0 && dim > 128) {
@@ -171,6 +177,9 @@ int enqueue_greedy(const void* table, int dtype, int64_t rows, int32_t dim, int6
     } else if (E == 0) {
         err = dtype == E4Q_F32 ? e4q::launch_greedy_rpl_tail_f32(a, dim, stream)
                                : e4q::launch_greedy_rpl_tail_f16(a, dim, stream);
+    } else if ((L & (L - 1)) != 0) {
+        err = dtype == E4Q_F32 ? e4q::launch_greedy_swl_any_f32(a, dim, E, L, stream)
+                               : e4q::launch_greedy_swl_any_f16(a, dim, E, L, stream);
     } else {
         if (E == 128)
             err = dtype == E4Q_F32 ? e4q::launch_greedy_swl_f32_big(a, dim, E, L, stream)

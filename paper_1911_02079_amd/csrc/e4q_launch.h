@@ -72,6 +72,9 @@ hipError_t launch_greedy_swl_f32_big(const GreedyArgs& a, int32_t dim, int E, in
 hipError_t launch_greedy_swl_f16_small(const GreedyArgs& a, int32_t dim, int E, int L, hipStream_t stream);
 hipError_t launch_greedy_swl_f16_mid(const GreedyArgs& a, int32_t dim, int E, int L, hipStream_t stream);
 hipError_t launch_greedy_swl_f16_big(const GreedyArgs& a, int32_t dim, int E, int L, hipStream_t stream);
+// The same with any number of lanes per row from 2 to 64 (a wave holds 64 / lanes rows): E in {8 .. 128}.
+hipError_t launch_greedy_swl_any_f32(const GreedyArgs& a, int32_t dim, int E, int lanes, hipStream_t stream);
+hipError_t launch_greedy_swl_any_f16(const GreedyArgs& a, int32_t dim, int E, int lanes, hipStream_t stream);
 
 // Arguments of the codebook (16-means) kernels.
 struct KMeansArgs {

@@ -65,9 +65,43 @@ __device__ __forceinline__ float group_reduce(float v, Op op)
     return v;
 }
 
+// The same reductions for a group of `lanes` neighbouring lanes, any number from 2 to 64 (L = 0 in the
+// templates below): lane `sub` of the group stands for leaf `sub` of a tree over next_pow2(lanes) leaves whose
+// missing leaves are empty.  Step s adds node sub + s to node sub where sub is a multiple of 2s and the
+// partner exists -- the adjacent pairs of the balanced tree, level by level -- and the group's first lane
+// ends with the result, which every lane then reads.  Lane values travel by ds_bpermute.
+__device__ __forceinline__ float lane_value(float v, int lane)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_ds_bpermute((lane & 63) << 2, __builtin_bit_cast(int, v)));
+}
+
+// Sum of non-negative terms: a lane that takes nothing in a step adds +0.0f, which changes nothing.
+__device__ __forceinline__ float group_sum_any(float v, int sub, int lanes)
+{
+    const int lane = (int)(threadIdx.x & 63u);
+    for (int s = 1; s < lanes; s <<= 1) {
+        const float t = lane_value(v, lane + s);
+        const bool take = (sub & (2 * s - 1)) == 0 && sub + s < lanes;
+        v = v + (take ? t : 0.0f);
+    }
+    return lane_value(v, lane - sub);
+}
+
+template <class Op>
+__device__ __forceinline__ float group_reduce_any(float v, int sub, int lanes, Op op)
+{
+    const int lane = (int)(threadIdx.x & 63u);
+    for (int s = 1; s < lanes; s <<= 1) {
+        const float t = lane_value(v, lane + s);
+        const bool take = (sub & (2 * s - 1)) == 0 && sub + s < lanes;
+        v = take ? op(v, t) : v;
+    }
+    return lane_value(v, lane - sub);
+}
+
 template <int E, int L, int MASK>
 __device__ __forceinline__ float swl_range_loss(const float (&x)[E], const float (&keep)[E], int nvalid, float lo,
-                                                float hi, float qmax)
+                                                float hi, float qmax, int sub, int lanes)
 {
     const StoredParams p = stored_params(lo, hi, qmax);
     float part;
@@ -82,20 +116,38 @@ __device__ __forceinline__ float swl_range_loss(const float (&x)[E], const float
     } else {
         part = tree_sq_err<0, E, E, MASK == 2>(x, p, nvalid, keep);
     }
-    return group_reduce<L>(part, [](float a, float b) { return a + b; });
+    if constexpr (L == 0) return group_sum_any(part, sub, lanes);
+    else return group_reduce<L>(part, [](float a, float b) { return a + b; });
 }
 
+// L = 0: `lanes` lanes per row, a run-time number that need not be a power of two; a wave then holds
+// 64 / lanes rows and its last 64 % lanes lanes idle (they redo a row and store nothing).
 template <int E, int L, typename Tin, int MASK>
-__global__ void __launch_bounds__(kSwlBlock) greedy_swl_kernel(GreedyArgs a, int32_t d)
+__global__ void __launch_bounds__(kSwlBlock) greedy_swl_kernel(GreedyArgs a, int32_t d, int32_t lanes_rt)
 {
     constexpr bool MASKED = MASK != 0;
     static_assert(E % 8 == 0 && (E & (E - 1)) == 0 && (L & (L - 1)) == 0 && L <= 64, "bad layout");
-    constexpr int kRowsPerBlock = kSwlBlock / L;
-    const int sub = threadIdx.x % L;
-    const int64_t row0 = linear_block() * kRowsPerBlock;
+    const int lanes = L != 0 ? L : lanes_rt;
+    int sub;
+    int64_t row0, row;
+    bool live;
+    if constexpr (L != 0) {
+        constexpr int kRowsPerBlock = kSwlBlock / L;
+        sub = threadIdx.x % L;
+        row0 = linear_block() * kRowsPerBlock;
+        row = row0 + threadIdx.x / L;
+        live = true;
+    } else {
+        const int rows_per_wave = 64 / lanes;
+        const int lane = (int)(threadIdx.x & 63u), wave = (int)(threadIdx.x >> 6);
+        const int group = lane / lanes;
+        sub = lane - group * lanes;
+        row0 = linear_block() * (int64_t)(rows_per_wave * (kSwlBlock / 64));
+        row = row0 + wave * rows_per_wave + group;
+        live = group < rows_per_wave;
+    }
     if (row0 >= a.rows) return;  // padding of a folded grid (no barrier in this kernel)
-    const int64_t row = row0 + threadIdx.x / L;
-    const bool live = row < a.rows;
+    live = live && row < a.rows;
     const int64_t r = live ? row : a.rows - 1;  // tail groups redo the last row and store nothing
     const int base = sub * E;
     const int nvalid = MASKED ? min(max(d - base, 0), E) : E;
@@ -128,8 +180,13 @@ __global__ void __launch_bounds__(kSwlBlock) greedy_swl_kernel(GreedyArgs a, int
         lo0 = __builtin_fminf(lo0, x[e]);
         hi0 = __builtin_fmaxf(hi0, x[e]);
     }
-    lo0 = group_reduce<L>(lo0, [](float p, float q) { return __builtin_fminf(p, q); });
-    hi0 = group_reduce<L>(hi0, [](float p, float q) { return __builtin_fmaxf(p, q); });
+    if constexpr (L == 0) {
+        lo0 = group_reduce_any(lo0, sub, lanes, [](float p, float q) { return __builtin_fminf(p, q); });
+        hi0 = group_reduce_any(hi0, sub, lanes, [](float p, float q) { return __builtin_fmaxf(p, q); });
+    } else {
+        lo0 = group_reduce<L>(lo0, [](float p, float q) { return __builtin_fminf(p, q); });
+        hi0 = group_reduce<L>(hi0, [](float p, float q) { return __builtin_fmaxf(p, q); });
+    }
     lo0 = canonical_zero(lo0);  // zero bounds are +0 whichever zeros the row holds
     hi0 = canonical_zero(hi0);
 
@@ -144,12 +201,12 @@ __global__ void __launch_bounds__(kSwlBlock) greedy_swl_kernel(GreedyArgs a, int
     if (a.n_iter > 0) {
         const float stepsize = (hi0 - lo0) / a.n_bins;
         float cur_lo = lo0, cur_hi = hi0;
-        float best = swl_range_loss<E, L, MASK>(x, keep, nvalid, lo0, hi0, a.qmax);
+        float best = swl_range_loss<E, L, MASK>(x, keep, nvalid, lo0, hi0, a.qmax, sub, lanes);
         for (int it = 0; it < a.n_iter; ++it) {
             const float next_lo = cur_lo + stepsize;
             const float next_hi = cur_hi - stepsize;
-            const float loss_l = swl_range_loss<E, L, MASK>(x, keep, nvalid, next_lo, cur_hi, a.qmax);
-            const float loss_r = swl_range_loss<E, L, MASK>(x, keep, nvalid, cur_lo, next_hi, a.qmax);
+            const float loss_l = swl_range_loss<E, L, MASK>(x, keep, nvalid, next_lo, cur_hi, a.qmax, sub, lanes);
+            const float loss_r = swl_range_loss<E, L, MASK>(x, keep, nvalid, cur_lo, next_hi, a.qmax, sub, lanes);
             const bool left = loss_l < loss_r;  // a tie moves the upper bound
             cur_lo = left ? next_lo : cur_lo;
             cur_hi = left ? cur_hi : next_hi;
@@ -189,7 +246,18 @@ inline hipError_t launch_greedy_swl(const GreedyArgs& a, int32_t d, hipStream_t 
 {
     constexpr int kRowsPerBlock = kSwlBlock / L;
     const int64_t blocks = (a.rows + kRowsPerBlock - 1) / kRowsPerBlock;
-    hipLaunchKernelGGL((greedy_swl_kernel<E, L, Tin, MASK>), grid_for(blocks), dim3(kSwlBlock), 0, stream, a, d);
+    hipLaunchKernelGGL((greedy_swl_kernel<E, L, Tin, MASK>), grid_for(blocks), dim3(kSwlBlock), 0, stream, a, d, L);
+    return hipGetLastError();
+}
+
+// `lanes` lanes per row, 2 .. 64, not necessarily a power of two.
+template <int E, typename Tin, int MASK>
+inline hipError_t launch_greedy_swl_any(const GreedyArgs& a, int32_t d, int32_t lanes, hipStream_t stream)
+{
+    if (lanes < 2 || lanes > 64 || (int64_t)E * lanes < d) return hipErrorInvalidValue;
+    const int64_t rows_per_block = (64 / lanes) * (kSwlBlock / 64);
+    const int64_t blocks = (a.rows + rows_per_block - 1) / rows_per_block;
+    hipLaunchKernelGGL((greedy_swl_kernel<E, 0, Tin, MASK>), grid_for(blocks), dim3(kSwlBlock), 0, stream, a, d, lanes);
     return hipGetLastError();
 }
 
@@ -209,6 +277,24 @@ hipError_t dispatch_greedy_swl(const GreedyArgs& a, int32_t d, int E, int L, hip
     }
     E4Q_SWL_LAYOUTS
 #undef E4Q_SWL
+    return hipErrorInvalidValue;
+}
+
+// The same for a lane count that is not a power of two: E from the list in E4Q_SWL_ANY_E.
+template <typename Tin>
+hipError_t dispatch_greedy_swl_any(const GreedyArgs& a, int32_t d, int E, int lanes, hipStream_t stream)
+{
+    const int mask = (d == E * lanes) ? 0 : (d % 8 == 0 ? 1 : 2);
+#define E4Q_SWL_E(EE)                                                                   \
+    if (E == EE) {                                                                      \
+        if (mask == 0) return launch_greedy_swl_any<EE, Tin, 0>(a, d, lanes, stream);   \
+        if (mask == 1) return launch_greedy_swl_any<EE, Tin, 1>(a, d, lanes, stream);   \
+        return launch_greedy_swl_any<EE, Tin, 2>(a, d, lanes, stream);                  \
+    }
+#ifdef E4Q_SWL_ANY_E
+    E4Q_SWL_ANY_E
+#endif
+#undef E4Q_SWL_E
     return hipErrorInvalidValue;
 }
 }  // namespace

@@ -172,7 +172,7 @@ def test_diagnostic_options(lib):
     assert lib.e4q_set_option(None, 1) == -8
     assert lib.e4q_set_option(b"kmeans_force_scan", 2) == -8
     assert lib.e4q_set_option(b"sls_nontemporal", -1) == -8
-    for bad in [(8 << 8) | 3, (8 << 8) | 128, (12 << 8) | 4, (128 << 8) | 64, (8 << 8), 2, -1]:
+    for bad in [(8 << 8) | 65, (8 << 8) | 128, (12 << 8) | 4, (128 << 8) | 64, (8 << 8), 2, -1]:
         assert lib.e4q_set_option(b"greedy_layout", bad) == -8
         assert lib.e4q_get_option(b"greedy_layout") == 0
     p = ctypes.c_void_p(0x1000)
@@ -199,6 +199,9 @@ def test_diagnostic_options(lib):
     assert cost(10_000_000, 128, 32, 1) > 0 and cost(10_000_000, 128, 32, (8 << 8) | 16) > cost(10_000_000, 128, 32, 1)
     assert cost(20_000, 128, 32, (16 << 8) | 8) < cost(20_000, 128, 32, 1)       # few rows: spread them over lanes
     assert cost(1000, 256, 32, 1) < 0 and cost(1000, 256, 32, (8 << 8) | 4) < 0 and cost(1000, 64, 32, 0) < 0
+    # a lane count that is not a power of two: 384 elements on 3 lanes beat 4 lanes of which one idles
+    assert 0 < cost(10_000_000, 384, 32, (128 << 8) | 3) < cost(10_000_000, 384, 32, (128 << 8) | 4)
+    assert cost(1000, 384, 32, (64 << 8) | 5) < 0
     assert lib.e4q_set_option(b"kmeans_force_scan", 1) == 0 and lib.e4q_get_option(b"kmeans_force_scan") == 1
     assert lib.e4q_set_option(b"kmeans_force_scan", 0) == 0
 

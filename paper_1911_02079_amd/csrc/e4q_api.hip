@@ -144,8 +144,9 @@ int enqueue_greedy(const void* table, int dtype, int64_t rows, int32_t dim, int6
         const bool rpl = e4q::rpl_supports_dim(dim) || e4q::rpl_tail_supports_dim(dim);
         double best = rpl ? layout_cost(rows, (dim + 7) / 8 * 8, 1, n_iter, true) : -1.0;
         // A dimension that is not a multiple of 8 carries one mask factor per element in a register of
-        // its own: with 32 elements per lane five waves per SIMD still fit, with 64 three, with 128 one.
-        const int e_max = dim % 8 == 0 ? 128 : (dim <= 2048 ? 32 : 64);
+        // its own: with 64 elements per lane three waves per SIMD still fit, with 128 one (measured on
+        // 128 M elements at dim 999: E = 32 1.33 ms, E = 64 1.28 ms, E = 128 2.76 ms).
+        const int e_max = dim % 8 == 0 ? 128 : 64;
         for (int e = 8; e <= e_max; e *= 2) {
             if (e > 8 && e / 2 >= dim) break;  // more than half of every lane would be padding
             // the fewest lanes that hold the row, and the next power of two (sums by DPP moves)

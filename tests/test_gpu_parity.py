@@ -324,6 +324,41 @@ def test_strided_and_unaligned_views(e4q, oracle_lib):
 
 
 @pytest.mark.parametrize("nbits", [2, 4, 8])
+@pytest.mark.parametrize("dim", [300, 320, 384, 768])
+def test_lane_counts_that_are_not_powers_of_two_on_views_and_guarded_outputs(e4q, oracle_lib, dim, nbits):
+    """Dimensions that take 3, 5 or 6 lanes per row (a wave then holds 21, 12 or 10 rows and its last lanes idle):
+    column slices of wider tables with 16-byte aligned and unaligned rows, a row count that leaves the last workgroup
+    partly empty, outputs at an odd byte offset between guard bytes."""
+    from paper_1911_02079_amd import synth
+
+    rows = 1003
+    for extra in (4, 1):
+        big = synth.outlier_table(rows, dim + extra, seed=6100 + dim + extra, device="cuda")
+        view = big[:, :dim]
+        nb = e4q.packed_bytes(dim, nbits)
+        cbuf = torch.full((rows * nb + 64,), 0xA5, dtype=torch.uint8, device="cuda")
+        sbuf = torch.full((rows + 16,), 1.5, dtype=torch.float16, device="cuda")
+        bbuf = torch.full((rows + 16,), 1.5, dtype=torch.float16, device="cuda")
+        out = (cbuf[31:31 + rows * nb].reshape(rows, nb), sbuf[8:8 + rows], bbuf[8:8 + rows])
+        say(f"dim={dim} nbits={nbits} row stride {dim + extra}, guarded outputs")
+        # what a large table of this dimension runs with; 1003 rows alone would be spread over 64 lanes each
+        layout = {300: (64, 5), 320: (64, 5), 384: (128, 3), 768: (128, 6)}[dim]
+        try:
+            e4q.set_option("greedy_layout", e4q.greedy_layout_value(layout))
+            e4q.quantize_rowwise_greedy(view, 50, 0.2, nbits=nbits, out=out)
+            torch.cuda.synchronize()
+        finally:
+            e4q.set_option("greedy_layout", 0)
+        assert e4q.get_option("greedy_layout_chosen") == e4q.greedy_layout_value(layout)
+        o = oracle_lib.quantize_rowwise_greedy(np.ascontiguousarray(view.cpu().numpy()), 50, 0.2, nbits=nbits)
+        assert np.array_equal(out[0].cpu().numpy(), o[0])
+        assert np.array_equal(f16_bits(out[1]), o[1]) and np.array_equal(f16_bits(out[2]), o[2])
+        assert bool((cbuf[:31] == 0xA5).all()) and bool((cbuf[31 + rows * nb:] == 0xA5).all())
+        for guard in (sbuf, bbuf):
+            assert bool((guard[:8] == 1.5).all()) and bool((guard[8 + rows:] == 1.5).all())
+
+
+@pytest.mark.parametrize("nbits", [2, 4, 8])
 @pytest.mark.parametrize("dim", [1, 3, 4, 5, 6, 7, 13, 50, 101, 127, 130])
 def test_dequantize_odd_dimensions_aligned_and_not(e4q, oracle_lib, dim, nbits):
     """dim % 4 != 0: four flattened elements per thread into a 16-byte aligned output (groups straddle row

@@ -143,18 +143,23 @@ int enqueue_greedy(const void* table, int dtype, int64_t rows, int32_t dim, int6
     } else {
         const bool rpl = e4q::rpl_supports_dim(dim) || e4q::rpl_tail_supports_dim(dim);
         double best = rpl ? layout_cost(rows, (dim + 7) / 8 * 8, 1, n_iter, true) : -1.0;
-        // A dimension that is not a multiple of 8 carries one mask factor per element in a register of
-        // its own: with 64 elements per lane three waves per SIMD still fit, with 128 one (measured on
-        // 128 M elements at dim 999: E = 32 1.33 ms, E = 64 1.28 ms, E = 128 2.76 ms).
-        const int e_max = dim % 8 == 0 ? 128 : 64;
-        for (int e = 8; e <= e_max; e *= 2) {
+        // A dimension that is not a multiple of 8 carries mask factors in registers of their own, one per
+        // element that some lane of the row's group may lack.  On the fewest lanes that hold the row only the
+        // last lane lacks any, and if it is at least half full the factors are few (greedy_swl.h).  64 elements
+        // per lane then measure best (128 M elements at dim 999: E = 32 1.40 ms, E = 64 1.21 ms, E = 128
+        // 1.31 ms; 2.76 ms for E = 128 with a factor per element, which leaves one wave per SIMD); 128 per lane
+        // only pay where 64 would leave most of a wave's lanes idle (dim 2500: 20 lanes of 128 1.73 ms, 40 or
+        // 64 lanes of 64 2.15 / 1.96 ms).
+        for (int e = 8; e <= 128; e *= 2) {
             if (e > 8 && e / 2 >= dim) break;  // more than half of every lane would be padding
             // the fewest lanes that hold the row, and the next power of two (sums by DPP moves)
             const int l_min = (dim + e - 1) / e;
             int l_pow2 = 1;
             while (l_pow2 < l_min) l_pow2 *= 2;
+            const bool few_factors = dim - (l_min - 1) * e >= e / 2;
             for (int l : {l_min, l_pow2}) {
                 if (l > 64) continue;
+                if (dim % 8 != 0 && e == 128 && !(l == l_min && few_factors && dim > 2048)) continue;
                 const double c = layout_cost(rows, e, l, n_iter, false);
                 if (best < 0.0 || c < best) {
                     best = c;
@@ -178,7 +183,9 @@ int enqueue_greedy(const void* table, int dtype, int64_t rows, int32_t dim, int6
     } else if (E == 0) {
         err = dtype == E4Q_F32 ? e4q::launch_greedy_rpl_tail_f32(a, dim, stream)
                                : e4q::launch_greedy_rpl_tail_f16(a, dim, stream);
-    } else if ((L & (L - 1)) != 0) {
+    } else if ((L & (L - 1)) != 0 || (dim % 8 != 0 && E >= 32 && L >= 2 && L == (dim + E - 1) / E)) {
+        // a lane count that is not a power of two, or the fewest lanes for a dimension that is not a multiple
+        // of 8: the run-time lane-count kernels have the variants with few mask factors
         err = dtype == E4Q_F32 ? e4q::launch_greedy_swl_any_f32(a, dim, E, L, stream)
                                : e4q::launch_greedy_swl_any_f16(a, dim, E, L, stream);
     } else {

@@ -20,7 +20,10 @@
 //     element then carries a lane mask, and 32 of them are what the scalar registers hold).
 // Masked instantiations take any dim <= E*L: elements at or beyond dim contribute exactly +0 to
 // the sums and are kept out of min/max.  MASK = 0: dim == E*L, no masking; MASK = 1: dim is a
-// multiple of 8, one select per block of 8 elements; MASK = 2: any dim, one select per element.
+// multiple of 8, one select per block of 8 elements; MASK = 2: any dim, one mask factor per element;
+// MASK = 3, 4, 5: the same for layouts in which every lane holds at least E/2, 3E/4, E - 8 elements (the
+// fewest lanes that hold the row, whose last lane is at least that full): only the elements from there on
+// carry a factor.
 #pragma once
 
 #include "e4q_device.h"
@@ -99,6 +102,9 @@ __device__ __forceinline__ float group_reduce_any(float v, int sub, int lanes, O
     return lane_value(v, lane - sub);
 }
 
+// Elements of a lane below this index exist in every lane of the layout.
+constexpr int swl_valid_below(int E, int MASK) { return MASK == 3 ? E / 2 : MASK == 4 ? 3 * E / 4 : MASK == 5 ? E - 8 : 0; }
+
 template <int E, int L, int MASK>
 __device__ __forceinline__ float swl_range_loss(const float (&x)[E], const float (&keep)[E], int nvalid, float lo,
                                                 float hi, float qmax, int sub, int lanes)
@@ -114,7 +120,7 @@ __device__ __forceinline__ float swl_range_loss(const float (&x)[E], const float
             return (blk < nblocks) ? bs : 0.0f;
         });
     } else {
-        part = tree_sq_err<0, E, E, MASK == 2>(x, p, nvalid, keep);
+        part = tree_sq_err<0, E, E, MASK >= 2, swl_valid_below(E, MASK)>(x, p, nvalid, keep);
     }
     if constexpr (L == 0) return group_sum_any(part, sub, lanes);
     else return group_reduce<L>(part, [](float a, float b) { return a + b; });
@@ -190,11 +196,12 @@ __global__ void __launch_bounds__(kSwlBlock) greedy_swl_kernel(GreedyArgs a, int
     lo0 = canonical_zero(lo0);  // zero bounds are +0 whichever zeros the row holds
     hi0 = canonical_zero(hi0);
 
-    // MASK = 2: one factor per element, 1.0f if it exists in this lane's part of the row (see tree_sq_err)
+    // MASK >= 2: one factor per element that may be missing, 1.0f if it exists in this lane's part of the row
+    // (see tree_sq_err)
     float keep[E];
-    if constexpr (MASK == 2) {
+    if constexpr (MASK >= 2) {
 #pragma unroll
-        for (int e = 0; e < E; ++e) keep[e] = lane_keep_factor(e < nvalid);
+        for (int e = swl_valid_below(E, MASK); e < E; ++e) keep[e] = lane_keep_factor(e < nvalid);
     }
 
     float best_lo = lo0, best_hi = hi0;
@@ -284,11 +291,18 @@ hipError_t dispatch_greedy_swl(const GreedyArgs& a, int32_t d, int E, int L, hip
 template <typename Tin>
 hipError_t dispatch_greedy_swl_any(const GreedyArgs& a, int32_t d, int E, int lanes, hipStream_t stream)
 {
-    const int mask = (d == E * lanes) ? 0 : (d % 8 == 0 ? 1 : 2);
+    int mask = (d == E * lanes) ? 0 : (d % 8 == 0 ? 1 : 2);
+    const int last = d - (lanes - 1) * E;  // elements in the row's last lane; every other lane is full if last > 0
+    if (mask == 2 && E >= 32) mask = last >= E - 8 ? 5 : last >= 3 * E / 4 ? 4 : last >= E / 2 ? 3 : 2;
 #define E4Q_SWL_E(EE)                                                                   \
     if (E == EE) {                                                                      \
         if (mask == 0) return launch_greedy_swl_any<EE, Tin, 0>(a, d, lanes, stream);   \
         if (mask == 1) return launch_greedy_swl_any<EE, Tin, 1>(a, d, lanes, stream);   \
+        if constexpr (EE >= 32) {                                                       \
+            if (mask == 3) return launch_greedy_swl_any<EE, Tin, 3>(a, d, lanes, stream); \
+            if (mask == 4) return launch_greedy_swl_any<EE, Tin, 4>(a, d, lanes, stream); \
+            if (mask == 5) return launch_greedy_swl_any<EE, Tin, 5>(a, d, lanes, stream); \
+        }                                                                               \
         return launch_greedy_swl_any<EE, Tin, 2>(a, d, lanes, stream);                  \
     }
 #ifdef E4Q_SWL_ANY_E

@@ -50,7 +50,7 @@ def layouts_for(dim):
 
 
 @pytest.mark.parametrize("half", [False, True], ids=["f32", "f16"])
-@pytest.mark.parametrize("dim", [32, 64, 100, 128, 136, 150, 192, 199, 200, 223, 224, 300, 320, 384, 768, 1000, 3000])
+@pytest.mark.parametrize("dim", [32, 64, 100, 128, 136, 150, 192, 199, 200, 223, 224, 250, 300, 320, 384, 768, 999, 1000, 1999, 3000])
 def test_every_forced_layout_matches_the_oracle(e4q, oracle_lib, dim, half):
     from paper_1911_02079_amd import synth
 

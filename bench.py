@@ -131,7 +131,8 @@ def bench_sls(args, e4q, synth, torch, gen, rows, dim, params) -> int:
     # context, outside the timed region: the same lookup from the three separate arrays, and from
     # records padded to one 128-byte line each
     three_ms = side_timing(lambda: e4q.sparse_lengths_sum(codes, scale, bias, dim, indices, offsets, out=out))
-    fused128 = e4q.fuse_rows(codes, scale, bias, dim, 128)
+    line_pitch = (e4q.fused_row_bytes(dim) + 127) // 128 * 128   # whole 128-byte lines per record
+    fused128 = e4q.fuse_rows(codes, scale, bias, dim, line_pitch)
     line_ms = side_timing(lambda: e4q.sparse_lengths_sum_fused(fused128, dim, indices, offsets, out=out))
     fuse_ms = side_timing(lambda: e4q.fuse_rows(codes, scale, bias, dim, pitch, out=fused))
     del fused128
@@ -167,17 +168,17 @@ def bench_sls(args, e4q, synth, torch, gen, rows, dim, params) -> int:
                    "bag_lengths": f"uniform 1..{params['max_len']}", "index_dtype": "int64",
                    "row_pitch": pitch, "nontemporal_gathers": bool(args.sls_nontemporal),
                    "step": f"sparse_lengths_sum_fused over all bags, fused records {pitch} bytes apart resident in HBM "
-                           f"({rows * pitch / 1e6:.0f} MB, not cache resident)"},
+                           f"({rows * pitch / 1e6:.1f} MB)"},
         "kernels": {"sls_fused_w8_kernel": {"avg_ms": ms, "lookups_per_s": n_lookups / (ms * 1e-3),
                                             "G_sums_per_s": sums / (ms * 1e-3) / 1e9, "row_pitch": pitch},
-                    "sls_fused_w8_kernel (row_pitch 128)": {"avg_ms": line_ms},
+                    f"sls_fused_w8_kernel (row_pitch {line_pitch})": {"avg_ms": line_ms},
                     "sls_w8_kernel (separate codes / scale / bias arrays)": {"avg_ms": three_ms},
                     "fuse_rows_w_kernel": {"avg_ms": fuse_ms}},
         "roofline": {"kernel": "sls_fused_w8_kernel", "bound": "hbm", "achieved": alg_bytes / (ms * 1e-3) / 1e9,
                      "peak": PEAK_HBM_BYTES / 1e9, "unit": "GB/s", "frac": alg_bytes / (ms * 1e-3) / PEAK_HBM_BYTES,
                      "bytes_per_lookup": dim // 2 + 4 + indices.element_size(), "bytes_per_bag": 4 * dim + 8,
                      "traffic": read_traffic(f"sls_fused_w8_kernel_{args.workload}_hbm_traffic.txt")
-                     if not (args.row_pitch or args.sls_nontemporal) else None},
+                     if not (args.row_pitch or args.sls_nontemporal or args.rows or args.dim) else None},
     }
     if not args.no_cpu_baseline:
         import oracle
@@ -291,7 +292,7 @@ def main() -> int:
     e4q.set_option("sls_nontemporal", 1 if args.sls_nontemporal else 0)
     method, gen, rows, dim, params = WORKLOADS[args.workload]
     if method == "sls":
-        return bench_sls(args, e4q, synth, torch, gen, rows, dim, params)
+        return bench_sls(args, e4q, synth, torch, gen, args.rows or rows, args.dim or dim, params)
     if method == "greedy_batch":
         return bench_batch(args, e4q, synth, torch, params)
     rows, dim = args.rows or rows, args.dim or dim

@@ -301,6 +301,8 @@ __global__ void __launch_bounds__(kSlsBlock) sls_fused_w8_kernel(const uint32_t*
         for (int w = 0; w < WPT; ++w) sls_add_word(acc[w], g.c[w], g.s, g.b);
     };
 
+    // Four gathers in flight per thread.  (Requesting the next four indices before the current records are added,
+    // to take their latency out of the index -> record -> add chain, measured 4 - 12 % slower.)
     int64_t i = begin;
     for (; i + 4 <= end; i += 4) {
         const Tidx i0 = indices[i], i1 = indices[i + 1], i2 = indices[i + 2], i3 = indices[i + 3];
@@ -328,9 +330,18 @@ static hipError_t launch_sls_fused_t(const uint8_t* fused, int64_t rows, int32_t
     const bool fast = dim % 8 == 0 && pitch % 4 == 0 && reinterpret_cast<uintptr_t>(fused) % 4 == 0 &&
                       reinterpret_cast<uintptr_t>(out) % 16 == 0;
     const int wpr = dim / 8;
+    // Code words per thread (4-, 8- or 16-byte gathers).  Measured on 34 M lookups, table of 10 M rows / of 20 000 rows
+    // (resident in L2), ms with 1 / 2 / 4 / 8 words per thread:
+    //   d =  64   0.91 / 0.99 / 1.00 / 1.00     0.64 / 0.51 / 0.45 / 0.47
+    //   d = 128   1.62 / 1.24 / 1.16 / 1.19     1.10 / 0.88 / 0.73 / 0.77
+    //   d = 256   2.78 / 2.12 / 1.87 / 1.89     1.88 / 1.56 / 1.33 / 1.40
+    //   d = 512   4.47 / 3.62 / 3.25 / 3.30     3.09 / 2.69 / 2.43 / 2.64
+    // so 16-byte gathers wherever the row allows them, except for short rows of tables far beyond the caches.
     int wpt = 1;
     if (fast) {
-        wpt = wpr % 2 == 0 ? 2 : 1;  // 8-byte gathers measured 6 % faster than 4-byte ones, 16-byte ones no better
+        const bool small_table = rows * pitch <= (int64_t)32 << 20;
+        if (wpr % 4 == 0 && (dim >= 128 || small_table)) wpt = 4;
+        else if (wpr % 2 == 0 && dim >= 128) wpt = 2;
     }
     const int64_t threads = fast ? n_bags * (wpr / wpt) : n_bags * ((dim + 7) / 8);
     const int64_t blocks = blocks_for(threads, kSlsBlock);
@@ -342,6 +353,12 @@ static hipError_t launch_sls_fused_t(const uint8_t* fused, int64_t rows, int32_t
     if (!fast)
         hipLaunchKernelGGL(sls_fused_h8_kernel<Tidx>, grid, block, 0, stream, fused, rows, (uint32_t)dim, pitch, idx,
                            n_indices, offsets, n_bags, out);
+    else if (wpt == 4 && nontemporal)
+        hipLaunchKernelGGL((sls_fused_w8_kernel<Tidx, 4, true>), grid, block, 0, stream, f32, rows, (uint32_t)wpr,
+                           (uint32_t)(pitch / 4), idx, n_indices, offsets, n_bags, o4);
+    else if (wpt == 4)
+        hipLaunchKernelGGL((sls_fused_w8_kernel<Tidx, 4, false>), grid, block, 0, stream, f32, rows, (uint32_t)wpr,
+                           (uint32_t)(pitch / 4), idx, n_indices, offsets, n_bags, o4);
     else if (wpt == 2 && nontemporal)
         hipLaunchKernelGGL((sls_fused_w8_kernel<Tidx, 2, true>), grid, block, 0, stream, f32, rows, (uint32_t)wpr,
                            (uint32_t)(pitch / 4), idx, n_indices, offsets, n_bags, o4);

@@ -480,6 +480,29 @@ def test_every_binade_of_scale(e4q, oracle_lib, dim, half, nbits):
     assert len(np.unique(o[1] >> 10)) >= 20   # the stored scales do span the binary16 exponents, subnormals included
 
 
+@pytest.mark.parametrize("dim", [8, 64, 100, 320])
+def test_binary32_subnormal_rows(e4q, oracle_lib, dim):
+    """Rows whose values are binary32 subnormals or just above them (2^-149 ... 2^-110): every stored scale
+    rounds to zero in binary16, ranges and step sizes are subnormal, and the kernels must treat such numbers as
+    the CPU does (no flush to zero), stored signs of zero included."""
+    from helpers import oracle_rows_in_parallel
+    from paper_1911_02079_amd import synth
+
+    rows = 64 * 9 + 3
+    t = synth.gaussian_table(rows, dim, 1.0, seed=8800 + dim, device="cuda")
+    k = (torch.arange(rows, device="cuda") % 40 - 149).to(torch.float32)          # -149 ... -110
+    t = (t.double() * torch.exp2(k.double())[:, None]).float()                    # rounds into the subnormal grid
+    assert bool((t.abs() < 1.2e-38).any()) and bool((t != 0).any())
+    say(f"subnormal rows dim={dim}")
+    codes, scale, bias = e4q.quantize_rowwise_greedy(t, 40, 0.3)
+    xh = e4q.dequantize(codes, scale, bias, dim)
+    torch.cuda.synchronize()
+    o = oracle_rows_in_parallel(oracle_lib, t.cpu().numpy(), 40, 0.3)
+    bad = np.flatnonzero((codes.cpu().numpy() != o[0]).any(axis=1) | (f16_bits(scale) != o[1]) | (f16_bits(bias) != o[2]))
+    assert bad.size == 0, f"{bad.size} rows differ, first {bad[:5]}"
+    assert np.array_equal(xh.cpu().numpy().view(np.uint32), oracle_lib.dequantize(o[0], o[1], o[2], dim).view(np.uint32))
+
+
 @pytest.mark.parametrize("dim,half", [(8, False), (64, True), (100, False), (128, False), (200, False), (512, True)])
 def test_rows_with_zeros_of_both_signs(e4q, oracle_lib, dim, half):
     """Sparse rows whose zeros carry either sign (what pruning or a binary16 conversion of tiny negative

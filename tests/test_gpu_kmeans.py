@@ -96,6 +96,27 @@ def test_dimensions_above_128(e4q, oracle_lib, dim, dtype):
     compare(e4q, oracle_lib, t, 7, f"chunked dim={dim}")
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.float16])
+@pytest.mark.parametrize("dim", [8, 16, 24, 64, 100, 200])
+def test_signed_zeros_and_tiny_rows(e4q, oracle_lib, dim, dtype):
+    """Sparse rows whose zeros carry either sign, rows of zeros only, and rows of binary32 subnormals or (for
+    binary16 tables) binary16 subnormals: centres, stored codebook bits (signs of zero included) and indices."""
+    from paper_1911_02079_amd import synth
+
+    rows = 64 * 7 + 5
+    g = torch.Generator(device="cuda").manual_seed(9300 + dim)
+    t = synth.gaussian_table(rows, dim, 0.1, seed=9200 + dim, device="cuda")
+    keep = torch.rand((rows, dim), device="cuda", generator=g) < 0.3
+    negzero = torch.rand((rows, dim), device="cuda", generator=g) < 0.5
+    t = torch.where(keep, t, torch.where(negzero, torch.full_like(t, -0.0), torch.zeros_like(t)))
+    t[1::7] = t[1::7].abs()
+    t[2::7] = -t[2::7].abs()
+    t[3::7] = torch.where(negzero[3::7], torch.full_like(t[3::7], -0.0), torch.zeros_like(t[3::7]))
+    tiny = 2.0 ** -20 if dtype == torch.float16 else 2.0 ** -140
+    t[5::7] = (t[5::7].double() * tiny).float()
+    compare(e4q, oracle_lib, t.to(dtype), 6, "signed zeros and tiny rows")
+
+
 def test_outputs_do_not_overrun(e4q):
     """Guard bands around indices and codebooks stay untouched (masked-tail rows staged through LDS, chunked
     rows, plain rows; ragged row counts)."""

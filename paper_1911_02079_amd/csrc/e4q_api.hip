@@ -472,6 +472,6 @@ const char* e4q_strerror(int code)
 
 const char* e4q_last_hip_error(void) { return g_hip_error; }
 
-int e4q_version(void) { return 300; }  // 0.3.0
+int e4q_version(void) { return 310; }  // 0.3.1
 
 }  // extern "C"

@@ -1,8 +1,9 @@
 // Greedy clip search with L lanes per row ("sub-wave layout"): lane j of a row's group keeps the
 // E contiguous elements [j*E, (j+1)*E) of the row in registers.
 //
-// The error sum of a range is an in-lane balanced tree over the lane's E elements followed by an
-// xor-butterfly over the L lanes of the group; with contiguous chunks per lane that is exactly the
+// The error sum of a range is an in-lane balanced tree over the lane's E elements followed by the upper
+// levels of the same tree across the L lanes of the group (an xor-butterfly of DPP moves when L is a power of
+// two, ds_bpermute steps for any other lane count); with contiguous chunks per lane that is exactly the
 // balanced tree over index-adjacent pairs of the whole (zero padded) row, so results are bit
 // identical to the one-row-per-lane kernels.  All L lanes of a group end up with the same sums and
 // take the same decisions.
@@ -14,10 +15,10 @@
 //     which a lone wave per SIMD cannot make up for (it issues only every fifth cycle);
 //   * ratio == 0 (plain min/max quantization, bound by HBM): with E = 8 a wave reads and writes
 //     contiguous memory;
-//   * dimensions above 128: E = 128 keeps the per-range scalar work (two divisions, two binary16
-//     round trips, ~45 instructions that every lane of the group repeats) small against 8
-//     operations for each of 128 elements; E <= 32 if the dimension is not a multiple of 8 (every
-//     element then carries a lane mask, and 32 of them are what the scalar registers hold).
+//   * dimensions above 224: E = 128 on ceil(dim / 128) lanes keeps the per-range scalar work (two short
+//     divisions, two binary16 round trips, ~30 instructions that every lane of the group repeats) small
+//     against 8 operations for each of 128 elements; E = 64 if the dimension is not a multiple of 8 (elements
+//     that a lane may lack carry a mask factor in a register of their own).
 // Masked instantiations take any dim <= E*L: elements at or beyond dim contribute exactly +0 to
 // the sums and are kept out of min/max.  MASK = 0: dim == E*L, no masking; MASK = 1: dim is a
 // multiple of 8, one select per block of 8 elements; MASK = 2: any dim, one mask factor per element;

@@ -91,6 +91,24 @@ def test_full_config3_laplace_10M_x_128(e4q, oracle_lib):
     assert np.array_equal(xh, want)
 
 
+@pytest.mark.parametrize("dim,half", [(8, False), (36, False), (199, False), (224, True), (300, False), (384, False),
+                                      (768, True), (999, False), (2500, False), (3000, False)])
+def test_sweep_dimensions_at_bench_scale(e4q, oracle_lib, dim, half):
+    """The dimension sweep of the measurements at a size where the library picks what it picks for large tables
+    (one row per lane with and without a masked tail, 3 / 5 / 6 / 16 / 20 / 32 lanes per row, mask factors for
+    part of a lane): 64 M elements per table, every row compared."""
+    from paper_1911_02079_amd import synth
+
+    rows = 64_000_000 // dim
+    table = synth.laplace_offset_table(rows, dim, seed=3100 + dim, device="cuda")
+    if half:
+        table = table.half()
+    full_compare(e4q, oracle_lib, table, 200, 0.16, f"sweep dim {dim}")
+    chosen = e4q.get_option("greedy_layout_chosen")
+    say(f"sweep dim {dim}: layout {'one row per lane' if chosen == 1 else (chosen >> 8, chosen & 0xff)}")
+    assert (chosen == 1) == (dim <= 224)
+
+
 def test_full_config4_batch_of_26_half_tables(e4q, oracle_lib):
     from paper_1911_02079_amd import synth
 

@@ -116,6 +116,9 @@ def test_batch_grouping(e4q, oracle_lib):
     tables.append(torch.empty((0, 64), device="cuda"))
     tables.append(synth.gaussian_table(777, 100, 0.1, seed=9200, device="cuda"))
     tables.append(synth.gaussian_table(50, 128, 0.1, seed=9201, device="cuda"))
+    # dimensions the grouped launches do not cover: one launch per table, in whatever layout the table takes
+    for k, (rows, dim) in enumerate([(40_000, 200), (30_000, 199), (50_000, 384), (20_000, 300), (9_000, 768), (700, 3000)]):
+        tables.append(synth.outlier_table(rows, dim, seed=9300 + k, device="cuda").to(torch.float16 if k % 2 else torch.float32))
     say(f"batch grouping: {len(tables)} tables")
     outs = e4q.quantize_rowwise_greedy_batch(tables, 200, 0.16)
     torch.cuda.synchronize()

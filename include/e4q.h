@@ -70,7 +70,7 @@ extern "C" {
  * what is stored.  ratio == 0 gives plain min/max ("ASYM") quantization.  A row with
  * max == min, or whose scale rounds to 0 in binary16, gets scale 0 and all codes 0.  A row's minimum
  * or maximum that is zero is taken as +0 whichever zeros the row holds (-0 = +0, and Algorithm 1 does
- * not say which one "min X" is), so a zero bias is stored as 0x0000.
+ * not say which one "min X" is): such a minimum is stored as the bias 0x0000, never 0x8000.
  *
  *   table       [in]  rows x dim elements of `dtype`, `row_stride` elements between rows
  *   dtype             E4Q_F32 or E4Q_F16 (binary16 inputs are widened exactly)

@@ -252,38 +252,51 @@ __global__ void __launch_bounds__(kCbBlock) dequantize_codebook_any_kernel(const
     }
 }
 
-// Any dim, out 16-byte aligned: four consecutive elements of the flattened output per thread (they may
-// straddle a row boundary), one 16-byte store per lane, one division per thread.
+// Any dim >= 4, out 16-byte aligned: four consecutive elements of the flattened output per thread (they may
+// straddle one row boundary), one 16-byte store per lane, one division per thread.  The four indices lie
+// within 24 bits of the index array (a row of odd dimension ends in 4 unused bits), so one unaligned 4-byte
+// read fetches them; threads whose read would pass the end of the array, or whose elements pass the end of
+// the table, take them byte by byte.
 template <bool WIDE>
 __global__ void __launch_bounds__(kCbBlock) dequantize_codebook_flat4_kernel(const uint8_t* __restrict__ idx,
                                                                              const uint16_t* __restrict__ cb,
-                                                                             int64_t n_elems, uint32_t dim,
-                                                                             float* __restrict__ out)
+                                                                             int64_t n_elems, int64_t n_idx_bytes,
+                                                                             uint32_t dim, float* __restrict__ out)
 {
     const int64_t e0 = (linear_block() * kCbBlock + threadIdx.x) * 4;
     if (e0 >= n_elems) return;
     const uint32_t nbytes = (dim + 1) / 2;
-    int64_t row = group_of<WIDE>(e0, dim);
-    uint32_t k = offset_in_group(e0, row, dim);
-    float v[4];
+    const int64_t row = group_of<WIDE>(e0, dim);
+    const uint32_t k = offset_in_group(e0, row, dim);
+    const int64_t byte0 = row * nbytes + k / 2;
+    if (e0 + 4 <= n_elems && byte0 + 4 <= n_idx_bytes) {
+        uint32_t w;
+        __builtin_memcpy(&w, idx + byte0, 4);
+        w >>= (k & 1u) * 4u;
+        const uint32_t in_row = dim - k;               // elements of this row among the four, if < 4
+        const uint32_t pad_bits = (dim & 1u) * 4u;     // unused bits at the end of a row
+        const uint16_t* book = cb + row * kK;
+        float v[4];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        v[j] = 0.0f;
-        if (e0 + j < n_elems) {
-            const uint32_t byte = idx[row * nbytes + k / 2];
-            const uint32_t q = (k & 1u) ? (byte >> 4) : (byte & 15u);
-            v[j] = f16_bits_to_float(cb[row * kK + q]);
+        for (uint32_t j = 0; j < 4; ++j) {
+            const bool next = j >= in_row;
+            const uint32_t q = (w >> (4u * j + (next ? pad_bits : 0u))) & 15u;
+            v[j] = f16_bits_to_float(book[(next ? kK : 0) + q]);  // the next row's codebook follows this one's
         }
-        if (++k == dim) {
-            k = 0;
-            ++row;
-        }
-    }
-    if (e0 + 4 <= n_elems) {
         floatx4 o = {v[0], v[1], v[2], v[3]};
         __builtin_nontemporal_store(o, reinterpret_cast<floatx4*>(out + e0));
-    } else {
-        for (int j = 0; e0 + j < n_elems; ++j) out[e0 + j] = v[j];
+        return;
+    }
+    int64_t r = row;
+    uint32_t c = k;
+    for (int j = 0; j < 4 && e0 + j < n_elems; ++j) {
+        const uint32_t byte = idx[r * nbytes + c / 2];
+        const uint32_t q = (c & 1u) ? (byte >> 4) : (byte & 15u);
+        out[e0 + j] = f16_bits_to_float(cb[r * kK + q]);
+        if (++c == dim) {
+            c = 0;
+            ++r;
+        }
     }
 }
 
@@ -306,13 +319,14 @@ hipError_t launch_dequantize_codebook(const uint8_t* idx, const uint16_t* centro
     } else {
         const int64_t n_elems = rows * dim;
         const int64_t blocks4 = blocks_for((n_elems + 3) / 4, kCbBlock);
-        if (reinterpret_cast<uintptr_t>(out) % 16 == 0 && blocks4 >= 0) {
+        if (reinterpret_cast<uintptr_t>(out) % 16 == 0 && blocks4 >= 0 && dim >= 4) {
+            const int64_t n_idx_bytes = rows * ((dim + 1) / 2);
             if (needs_wide_index(n_elems))
                 hipLaunchKernelGGL(dequantize_codebook_flat4_kernel<true>, grid_for(blocks4), dim3(kCbBlock), 0,
-                                   stream, idx, centroids_f16, n_elems, (uint32_t)dim, out);
+                                   stream, idx, centroids_f16, n_elems, n_idx_bytes, (uint32_t)dim, out);
             else
                 hipLaunchKernelGGL(dequantize_codebook_flat4_kernel<false>, grid_for(blocks4), dim3(kCbBlock), 0,
-                                   stream, idx, centroids_f16, n_elems, (uint32_t)dim, out);
+                                   stream, idx, centroids_f16, n_elems, n_idx_bytes, (uint32_t)dim, out);
         } else {
             int64_t blocks = (n_elems + kCbBlock - 1) / kCbBlock;
             if (blocks > kMaxGridX) blocks = kMaxGridX;  // the kernel loops over what is left

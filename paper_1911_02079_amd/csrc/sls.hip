@@ -17,31 +17,49 @@ namespace e4q {
 constexpr int kSlsBlock = 256;
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
+// Adds the eight de-quantized codes of one 32-bit word.  The even and the odd nibbles are first spread over the
+// bytes of two words, so that each code is one byte-to-float conversion away (two masks and a shift per word
+// instead of a bit-field extract per code).
 __device__ __forceinline__ void sls_add_word(float (&acc)[8], uint32_t c, float s, float b)
 {
+    uint32_t even = c & 0x0f0f0f0fu, odd = (c >> 4) & 0x0f0f0f0fu;
+    asm("" : "+v"(even));  // or the optimizer folds the masks back into one extract per code
+    asm("" : "+v"(odd));
 #pragma unroll
-    for (int e = 0; e < 8; ++e) acc[e] = acc[e] + __builtin_fmaf((float)((c >> (4 * e)) & 15u), s, b);
+    for (int k = 0; k < 4; ++k) {
+        acc[2 * k] = acc[2 * k] + __builtin_fmaf((float)((even >> (8 * k)) & 0xffu), s, b);
+        acc[2 * k + 1] = acc[2 * k + 1] + __builtin_fmaf((float)((odd >> (8 * k)) & 0xffu), s, b);
+    }
 }
 
+// A gathered row as it was read: one word of codes, the binary16 scale and bias, and whether the index was inside
+// the table.  Nothing is converted or dropped before all the rows in flight have been requested (no branch and
+// no wait between the loads of different rows); an index outside the table reads row 0 and is dropped when
+// it is added (scale = bias = 0 make every term fma(q, 0, 0) = +0).  Needs rows > 0.
 struct SlsRow {
     uint32_t c;
-    float s, b;
+    uint16_t s, b;
+    bool ok;
 };
 
-// Gathers word `word` of row r (all zero, which adds +0, when r is out of range).
 template <typename Tidx>
 __device__ __forceinline__ SlsRow sls_gather(const uint32_t* __restrict__ codes, const uint16_t* __restrict__ sc,
                                              const uint16_t* __restrict__ bi, int64_t rows, uint32_t wpr,
                                              uint32_t word, Tidx idx)
 {
     const int64_t r = (int64_t)idx;
-    const bool ok = r >= 0 && r < rows;
-    const int64_t rr = ok ? r : 0;
     SlsRow g;
-    g.c = ok ? codes[rr * wpr + word] : 0u;
-    g.s = ok ? f16_bits_to_float(sc[rr]) : 0.0f;
-    g.b = ok ? f16_bits_to_float(bi[rr]) : 0.0f;
+    g.ok = r >= 0 && r < rows;
+    const int64_t rr = g.ok ? r : 0;
+    g.c = codes[rr * wpr + word];
+    g.s = sc[rr];
+    g.b = bi[rr];
     return g;
+}
+
+__device__ __forceinline__ void sls_add_row(float (&acc)[8], const SlsRow& g)
+{
+    sls_add_word(acc, g.c, f16_bits_to_float(g.ok ? g.s : (uint16_t)0), f16_bits_to_float(g.ok ? g.b : (uint16_t)0));
 }
 
 // dim % 8 == 0, codes 4-byte aligned, out 16-byte aligned.
@@ -60,7 +78,7 @@ __global__ void __launch_bounds__(kSlsBlock) sls_w8_kernel(const uint32_t* __res
     const uint32_t word = offset_in_group(t, bag, wpr);
     const int64_t lo = offsets[bag], hi = offsets[bag + 1];
     const int64_t begin = lo < 0 ? 0 : (lo > n_indices ? n_indices : lo);
-    const int64_t end = hi < begin ? begin : (hi > n_indices ? n_indices : hi);
+    const int64_t end = (hi < begin || rows == 0) ? begin : (hi > n_indices ? n_indices : hi);  // empty table: no row 0
 
     float acc[8] = {0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f, 0.0f};
     int64_t i = begin;
@@ -70,19 +88,23 @@ __global__ void __launch_bounds__(kSlsBlock) sls_w8_kernel(const uint32_t* __res
         const SlsRow g1 = sls_gather(codes, sc, bi, rows, wpr, word, i1);
         const SlsRow g2 = sls_gather(codes, sc, bi, rows, wpr, word, i2);
         const SlsRow g3 = sls_gather(codes, sc, bi, rows, wpr, word, i3);
-        sls_add_word(acc, g0.c, g0.s, g0.b);
-        sls_add_word(acc, g1.c, g1.s, g1.b);
-        sls_add_word(acc, g2.c, g2.s, g2.b);
-        sls_add_word(acc, g3.c, g3.s, g3.b);
+        __builtin_amdgcn_sched_barrier(0);  // all twelve loads are on their way before the first row is unpacked
+        sls_add_row(acc, g0);
+        sls_add_row(acc, g1);
+        sls_add_row(acc, g2);
+        sls_add_row(acc, g3);
     }
-    for (; i < end; ++i) {
-        const SlsRow g = sls_gather(codes, sc, bi, rows, wpr, word, indices[i]);
-        sls_add_word(acc, g.c, g.s, g.b);
-    }
+    for (; i < end; ++i) sls_add_row(acc, sls_gather(codes, sc, bi, rows, wpr, word, indices[i]));
     floatx4 v0 = {acc[0], acc[1], acc[2], acc[3]}, v1 = {acc[4], acc[5], acc[6], acc[7]};
     out[2 * t] = v0;
     out[2 * t + 1] = v1;
 }
+
+// The same row with its parameters already widened (the generic kernels below fill it piece by piece).
+struct SlsRowF {
+    uint32_t c;
+    float s, b;
+};
 
 // Any dim, pitch and alignment, 8 elements per thread: the loop shared by the two kernels below.
 // `gather(r)` returns code word `word` of row r (bytes beyond the row's codes read as 0) and its
@@ -100,14 +122,14 @@ __device__ __forceinline__ void sls_bytes_body(Gather&& gather, uint32_t dim, ui
     int64_t i = begin;
     for (; i + 4 <= end; i += 4) {
         const Tidx i0 = indices[i], i1 = indices[i + 1], i2 = indices[i + 2], i3 = indices[i + 3];
-        const SlsRow g0 = gather((int64_t)i0), g1 = gather((int64_t)i1), g2 = gather((int64_t)i2), g3 = gather((int64_t)i3);
+        const SlsRowF g0 = gather((int64_t)i0), g1 = gather((int64_t)i1), g2 = gather((int64_t)i2), g3 = gather((int64_t)i3);
         sls_add_word(acc, g0.c, g0.s, g0.b);
         sls_add_word(acc, g1.c, g1.s, g1.b);
         sls_add_word(acc, g2.c, g2.s, g2.b);
         sls_add_word(acc, g3.c, g3.s, g3.b);
     }
     for (; i < end; ++i) {
-        const SlsRow g = gather((int64_t)indices[i]);
+        const SlsRowF g = gather((int64_t)indices[i]);
         sls_add_word(acc, g.c, g.s, g.b);
     }
     float* o = out + bag * dim + 8 * word;
@@ -142,7 +164,7 @@ __global__ void __launch_bounds__(kSlsBlock) sls_bytes_kernel(const uint8_t* __r
     const int64_t bag = group_of(t, n_threads, wpr);
     const uint32_t word = offset_in_group(t, bag, wpr);
     sls_bytes_body<Tidx>([&](int64_t r) {
-        SlsRow g = {0u, 0.0f, 0.0f};
+        SlsRowF g = {0u, 0.0f, 0.0f};
         if (r >= 0 && r < rows) {
             g.c = sls_code_bytes(codes + r * nbytes, 4 * word, nbytes);
             g.s = f16_bits_to_float(sc[r]);
@@ -169,7 +191,7 @@ __global__ void __launch_bounds__(kSlsBlock) sls_fused_h8_kernel(const uint8_t* 
     const int64_t bag = group_of(t, n_threads, wpr);
     const uint32_t word = offset_in_group(t, bag, wpr);
     sls_bytes_body<Tidx>([&](int64_t r) {
-        SlsRow g = {0u, 0.0f, 0.0f};
+        SlsRowF g = {0u, 0.0f, 0.0f};
         if (r >= 0 && r < rows) {
             // both halves of the word lie inside the record (its parameters follow the codes)
             const uint16_t* h = reinterpret_cast<const uint16_t*>(fused + r * pitch);
@@ -246,7 +268,7 @@ hipError_t launch_fuse_rows(const uint8_t* codes, const uint16_t* sc, const uint
 
 // Lookup over fused records; dim % 8 == 0, pitch % 4 == 0, 4-byte aligned records, 16-byte aligned out.
 // One thread owns WPT consecutive code words (8 * WPT elements) of one bag.
-template <typename Tidx, int WPT, bool NT>
+template <typename Tidx, int WPT, bool NT, int G = 4>
 __global__ void __launch_bounds__(kSlsBlock) sls_fused_w8_kernel(const uint32_t* __restrict__ fused, int64_t rows,
                                                                  uint32_t wpr, uint32_t pitch_words,
                                                                  const Tidx* __restrict__ indices, int64_t n_indices,
@@ -262,33 +284,34 @@ __global__ void __launch_bounds__(kSlsBlock) sls_fused_w8_kernel(const uint32_t*
     const uint32_t word = offset_in_group(t, bag, tpb) * WPT;
     const int64_t lo = offsets[bag], hi = offsets[bag + 1];
     const int64_t begin = lo < 0 ? 0 : (lo > n_indices ? n_indices : lo);
-    const int64_t end = hi < begin ? begin : (hi > n_indices ? n_indices : hi);
+    const int64_t end = (hi < begin || rows == 0) ? begin : (hi > n_indices ? n_indices : hi);
 
+    // A gathered record as it was read.  Scale and bias are converted, and a record of an index outside the table
+    // is dropped, only when the record is added: the loads of all records in flight are issued first, and
+    // nothing that waits for one of them stands between them.
     struct Rec {
         uint32_t c[WPT];
-        float s, b;
+        uint32_t sb;  // scale in the low half, bias in the high half
+        bool ok;      // the index was inside the table
     };
+    // No branch: an index outside the table reads record 0, which is dropped later (scale = bias = 0 make every
+    // term fma(q, 0, 0) = +0, whatever the codes).  With a branch per record the gathers of a round sit in
+    // separate basic blocks and each waits for the one before it.  An empty table is kept away from here (no
+    // record 0 to read: the bag loops then run over nothing).
     auto gather = [&](Tidx idx) {
         const int64_t r = (int64_t)idx;
-        const bool ok = r >= 0 && r < rows;
         Rec g;
-        uint32_t sb = 0u;  // scale and bias 0 and codes 0: the row adds +0
+        g.ok = r >= 0 && r < rows;
+        const uint32_t* rec = fused + (g.ok ? r : 0) * pitch_words;
+        g.sb = NT ? __builtin_nontemporal_load(rec + wpr) : rec[wpr];
+        if constexpr (WPT == 1) {
+            g.c[0] = NT ? __builtin_nontemporal_load(rec + word) : rec[word];
+        } else {
+            const words_t* pv = reinterpret_cast<const words_t*>(rec + word);
+            const words_t v = NT ? __builtin_nontemporal_load(pv) : *pv;
 #pragma unroll
-        for (int w = 0; w < WPT; ++w) g.c[w] = 0u;
-        if (ok) {  // nothing is read for an index outside the table (which may be empty: fused == NULL)
-            const uint32_t* rec = fused + r * pitch_words;
-            sb = NT ? __builtin_nontemporal_load(rec + wpr) : rec[wpr];
-            if constexpr (WPT == 1) {
-                g.c[0] = NT ? __builtin_nontemporal_load(rec + word) : rec[word];
-            } else {
-                const words_t* pv = reinterpret_cast<const words_t*>(rec + word);
-                const words_t v = NT ? __builtin_nontemporal_load(pv) : *pv;
-#pragma unroll
-                for (int w = 0; w < WPT; ++w) g.c[w] = v[w];
-            }
+            for (int w = 0; w < WPT; ++w) g.c[w] = v[w];
         }
-        g.s = f16_bits_to_float((uint16_t)(sb & 0xffffu));
-        g.b = f16_bits_to_float((uint16_t)(sb >> 16));
         return g;
     };
     float acc[WPT][8];
@@ -297,20 +320,25 @@ __global__ void __launch_bounds__(kSlsBlock) sls_fused_w8_kernel(const uint32_t*
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[w][e] = 0.0f;
     auto add = [&](const Rec& g) {
+        const uint32_t sb = g.ok ? g.sb : 0u;
+        const float sc = f16_bits_to_float((uint16_t)(sb & 0xffffu)), bi = f16_bits_to_float((uint16_t)(sb >> 16));
 #pragma unroll
-        for (int w = 0; w < WPT; ++w) sls_add_word(acc[w], g.c[w], g.s, g.b);
+        for (int w = 0; w < WPT; ++w) sls_add_word(acc[w], g.c[w], sc, bi);
     };
 
     // Four gathers in flight per thread.  (Requesting the next four indices before the current records are added,
     // to take their latency out of the index -> record -> add chain, measured 4 - 12 % slower.)
     int64_t i = begin;
-    for (; i + 4 <= end; i += 4) {
-        const Tidx i0 = indices[i], i1 = indices[i + 1], i2 = indices[i + 2], i3 = indices[i + 3];
-        const Rec g0 = gather(i0), g1 = gather(i1), g2 = gather(i2), g3 = gather(i3);
-        add(g0);
-        add(g1);
-        add(g2);
-        add(g3);
+    for (; i + G <= end; i += G) {
+        Tidx ix[G];
+#pragma unroll
+        for (int k = 0; k < G; ++k) ix[k] = indices[i + k];
+        Rec g[G];
+#pragma unroll
+        for (int k = 0; k < G; ++k) g[k] = gather(ix[k]);
+        __builtin_amdgcn_sched_barrier(0);  // all the loads are on their way before the first record is unpacked
+#pragma unroll
+        for (int k = 0; k < G; ++k) add(g[k]);
     }
     for (; i < end; ++i) add(gather(indices[i]));
     floatx4* o = out + 2 * (bag * wpr + word);
@@ -331,12 +359,12 @@ static hipError_t launch_sls_fused_t(const uint8_t* fused, int64_t rows, int32_t
                       reinterpret_cast<uintptr_t>(out) % 16 == 0;
     const int wpr = dim / 8;
     // Code words per thread (4-, 8- or 16-byte gathers).  Measured on 34 M lookups, table of 10 M rows / of 20 000 rows
-    // (resident in L2), ms with 1 / 2 / 4 / 8 words per thread:
-    //   d =  64   0.91 / 0.99 / 1.00 / 1.00     0.64 / 0.51 / 0.45 / 0.47
-    //   d = 128   1.62 / 1.24 / 1.16 / 1.19     1.10 / 0.88 / 0.73 / 0.77
-    //   d = 256   2.78 / 2.12 / 1.87 / 1.89     1.88 / 1.56 / 1.33 / 1.40
-    //   d = 512   4.47 / 3.62 / 3.25 / 3.30     3.09 / 2.69 / 2.43 / 2.64
+    // (resident in L2), ms with 1 / 2 / 4 words per thread:
+    //   d =  64   0.87 / 0.90 / 0.98     0.47 / 0.46 / 0.42
+    //   d = 128   1.13 / 1.15 / 1.12     0.79 / 0.76 / 0.63
+    //   d = 512   3.10 / 3.36 / 2.94     2.16 / 2.41 / 2.05
     // so 16-byte gathers wherever the row allows them, except for short rows of tables far beyond the caches.
+    // Records in flight per thread: 2 / 4 / 8 measure 1.20 / 1.12 / 1.12 ms at d = 128 (0.77 / 0.63 / 0.64 resident).
     int wpt = 1;
     if (fast) {
         const bool small_table = rows * pitch <= (int64_t)32 << 20;

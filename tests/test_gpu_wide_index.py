@@ -1,4 +1,4 @@
-"""Tables with more than 2^32 groups or elements: the de-quantizers' 64-bit index paths.
+"""Tables with more than 2^32 groups or elements: the 64-bit index paths of the de-quantizers and of the search.
 
 The paper's own tables (50 M rows of 128 values, Section 5) have 6.4e9 elements.  The codes here are
 random bytes (any byte string is a valid packed row) and the outputs are compared with the oracle on
@@ -96,6 +96,39 @@ def test_codebook_dequantize_beyond_2_pow_32(e4q, oracle_lib):
     bad = np.flatnonzero((got.view(np.uint32) != want.view(np.uint32)).any(axis=1))
     assert bad.size == 0, f"rows {picks[bad[:5]]} differ"
     del out, idx
+    torch.cuda.empty_cache()
+
+
+def test_greedy_on_a_table_of_the_papers_size(e4q, oracle_lib):
+    """50 M rows x 128 binary32 (the largest tables of Section 5; 6.4e9 elements, 25.6 GB): Algorithm 1 at its
+    defaults over the whole table in one call, then compared with the oracle on both ends, on the rows on either side
+    of element number 2^32, and on a strided sample; de-quantized rows of the same sample as well."""
+    from helpers import oracle_rows_in_parallel
+    from paper_1911_02079_amd import synth
+
+    rows, dim = 50_000_000, 128
+    say(f"paper-size table: drawing {rows} x {dim} binary32 ({rows * dim * 4 / 1e9:.1f} GB)")
+    table = synth.laplace_offset_table(rows, dim, seed=5050, device="cuda")
+    out = e4q.alloc_outputs(rows, dim, table.device)
+    say("paper-size table: GPU quantize")
+    e4q.quantize_rowwise_greedy(table, 200, 0.16, out=out)
+    torch.cuda.synchronize()
+    assert e4q.get_option("greedy_layout_chosen") == 1  # one row per lane
+    picks = np.unique(np.concatenate([sample_rows(rows, dim, 1 << 32), np.arange(0, rows, 499)]))
+    sel = torch.from_numpy(picks).cuda()
+    say(f"paper-size table: oracle on {picks.size} sampled rows")
+    o_codes, o_scale, o_bias = oracle_rows_in_parallel(oracle_lib, table[sel].cpu().numpy(), 200, 0.16)
+    bad = np.flatnonzero((out[0][sel].cpu().numpy() != o_codes).any(axis=1) | (f16_bits(out[1][sel]) != o_scale) |
+                         (f16_bits(out[2][sel]) != o_bias))
+    assert bad.size == 0, f"rows {picks[bad[:5]]} differ"
+    del table
+    torch.cuda.empty_cache()
+    say("paper-size table: de-quantize and compare the same rows")
+    xh = e4q.dequantize(*out, dim)
+    torch.cuda.synchronize()
+    want = oracle_lib.dequantize(o_codes, o_scale, o_bias, dim)
+    assert np.array_equal(xh[sel].cpu().numpy().view(np.uint32), want.view(np.uint32))
+    del xh, out
     torch.cuda.empty_cache()
 
 

@@ -264,7 +264,8 @@ def main() -> int:
     ap.add_argument("--nbits", type=int, default=4, choices=[2, 4, 8], help="code width of the uniform quantizer")
     ap.add_argument("--layout", default="auto",
                     help="thread layout of the greedy search: auto (the library's cost model), rpl (one row per "
-                         "lane) or E,L (L lanes per row, E elements each), through the greedy_layout diagnostic option")
+                         "lane), E,L (L lanes per row, E elements each) or E,L,twin (two such groups per row, one per candidate "
+                         "range of a trip), through the greedy_layout diagnostic option")
     ap.add_argument("--row-pitch", type=int, default=0,
                     help="lookup workload: bytes between fused records (default: the smallest record, d/2 + 4)")
     ap.add_argument("--sls-nontemporal", action="store_true", help="lookup workload: non-temporal record gathers")
@@ -317,7 +318,7 @@ def main() -> int:
         torch.cuda.synchronize()
         chosen = e4q.get_option("greedy_layout_chosen")
         rpl = chosen == 1
-        layout = "one row per lane" if rpl else f"E={chosen >> 8} elements x L={chosen & 0xff} lanes per row"
+        layout = e4q.greedy_layout_name(chosen)
         q_name, dq_name = ("greedy_rpl_kernel" if rpl else "greedy_swl_kernel"), "dequantize_w4_kernel"
         ops_per_row = greedy_lane_ops_per_row(dim, n_iter)
         out_bytes_per_row = e4q.packed_bytes(dim, nbits) + 4

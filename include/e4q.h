@@ -221,6 +221,10 @@ int32_t e4q_greedy_iterations(int32_t n_bins, float ratio);
  *                        (E << 8) | L: L lanes per row with E contiguous elements each,
  *                        E in {8, 16, 32, 64, 128}, 1 <= L <= 64 (not 64 for E = 128); an L that is not a
  *                        power of two leaves 64 % L lanes of every wave idle.
+ *                        (1 << 16) | (E << 8) | L: two such groups of L lanes per row, each holding the whole
+ *                        row; the two candidate ranges of every trip of Algorithm 1's loop are scored at the
+ *                        same time, one by each group (for small tables, where the duration of the launch is
+ *                        the duration of one wave).  E in {8, 16}, L a power of two up to 32.
  *                        A forced layout needs E * L >= dim; the quantize calls return
  *                        E4Q_ERR_BAD_OPTION otherwise.  The batch call then launches table by table.
  *   "kmeans_force_scan"  1: e4q_quantize_rowwise_kmeans16 scans all 16 centres for every value

@@ -20,7 +20,7 @@ def __getattr__(name):
     if name in ("quantize_rowwise_greedy", "quantize_rowwise_greedy_batch", "dequantize", "greedy_iterations",
                 "alloc_outputs", "packed_bytes", "load_library", "E4QError", "quantize_rowwise_kmeans16", "dequantize_codebook",
                 "sparse_lengths_sum", "fuse_rows", "sparse_lengths_sum_fused", "fused_row_bytes", "set_option", "get_option",
-                "greedy_layout_value", "greedy_layout_cost"):
+                "greedy_layout_value", "greedy_layout_cost", "greedy_layout_name", "GREEDY_LAYOUT_TWIN"):
         import importlib
 
         return getattr(importlib.import_module(".binding", __name__), name)

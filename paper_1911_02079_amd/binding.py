@@ -151,15 +151,33 @@ def greedy_layout_cost(rows: int, dim: int, n_iter: int, layout) -> float:
     return float(load_library().e4q_greedy_layout_cost(int(rows), int(dim), int(n_iter), value))
 
 
+GREEDY_LAYOUT_TWIN = 1 << 16  # flag of a layout value: two groups of L lanes per row, one per candidate range of a trip
+
+
 def greedy_layout_value(layout) -> int:
     """Value of the "greedy_layout" option: None or "auto" -> 0, "rpl" -> 1 (one row per lane),
-    (E, L) or "E,L" -> (E << 8) | L."""
+    (E, L) or "E,L" -> (E << 8) | L, (E, L, True) or "E,L,twin" -> the same with the twin flag."""
     if layout is None or layout == "auto":
         return 0
     if layout == "rpl":
         return 1
-    e, l = (int(v) for v in layout.split(",")) if isinstance(layout, str) else layout
-    return (int(e) << 8) | int(l)
+    parts = layout.split(",") if isinstance(layout, str) else list(layout)
+    twin = len(parts) == 3 and parts[2] in (True, 1, "twin", "1")
+    if len(parts) not in (2, 3) or (len(parts) == 3 and not twin):
+        raise ValueError('layout must be "auto", "rpl", "E,L" or "E,L,twin"')
+    return (GREEDY_LAYOUT_TWIN if twin else 0) | (int(parts[0]) << 8) | int(parts[1])
+
+
+def greedy_layout_name(value: int) -> str:
+    """Readable form of a "greedy_layout" / "greedy_layout_chosen" value."""
+    if value == 0:
+        return "automatic"
+    if value == 1:
+        return "one row per lane"
+    e, lanes = (value & ~GREEDY_LAYOUT_TWIN) >> 8, value & 0xFF
+    if value & GREEDY_LAYOUT_TWIN:
+        return f"E={e} elements x 2 groups of L={lanes} lanes per row (one group per candidate range)"
+    return f"E={e} elements x L={lanes} lanes per row"
 
 
 def packed_bytes(dim: int, nbits: int = 4) -> int:

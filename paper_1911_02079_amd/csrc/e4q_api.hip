@@ -23,7 +23,10 @@ int fail_launch(hipError_t err)
 }
 
 // Diagnostic options (e4q_set_option): process-wide, read once per call.
-std::atomic<int64_t> g_greedy_layout{0};      // 0 automatic, 1 one row per lane, (E << 8) | L sub-wave layout
+// 0 automatic, 1 one row per lane, (E << 8) | L sub-wave layout, kTwin | (E << 8) | L the same with two groups of
+// L lanes per row (one per candidate range of a trip)
+std::atomic<int64_t> g_greedy_layout{0};
+constexpr int64_t kTwin = (int64_t)1 << 16;
 std::atomic<int64_t> g_kmeans_force_scan{0};  // 1: scan all 16 centres instead of bisecting
 std::atomic<int64_t> g_sls_nontemporal{0};    // 1: gather records with non-temporal loads
 std::atomic<int64_t> g_greedy_layout_chosen{0};  // read-only: layout of the last single-table greedy launch
@@ -41,6 +44,11 @@ std::atomic<int64_t>* find_option(const char* name)
 bool layout_value_ok(int64_t v)
 {
     if (v == 0 || v == 1) return true;
+    if (v < 0 || v >= 2 * kTwin) return false;
+    if (v & kTwin) {  // instantiated for 8 and 16 elements per lane, two groups of at most 32 lanes
+        const int64_t e = (v & ~kTwin) >> 8, l = v & 0xff;
+        return (e == 8 || e == 16) && l >= 1 && l <= 32 && (l & (l - 1)) == 0;
+    }
     const int64_t e = v >> 8, l = v & 0xff;
     if (e != 8 && e != 16 && e != 32 && e != 64 && e != 128) return false;
     if (l < 1 || l > 64) return false;
@@ -77,7 +85,7 @@ int validate_forced_layout(int32_t dim)
     const int64_t forced = g_greedy_layout.load(std::memory_order_relaxed);
     if (forced == 0) return E4Q_OK;
     if (forced == 1) return (e4q::rpl_supports_dim(dim) || e4q::rpl_tail_supports_dim(dim)) ? E4Q_OK : E4Q_ERR_BAD_OPTION;
-    return (forced >> 8) * (forced & 0xff) >= dim ? E4Q_OK : E4Q_ERR_BAD_OPTION;
+    return ((forced & ~kTwin) >> 8) * (forced & 0xff) >= dim ? E4Q_OK : E4Q_ERR_BAD_OPTION;
 }
 
 // Estimated duration of the greedy search, in SIMD cycles, for `rows` rows with `elems` elements per
@@ -85,9 +93,13 @@ int validate_forced_layout(int32_t dim)
 // per-range scalar work (two short divisions, two binary16 round trips, the decisions) and 6 per butterfly
 // step.  Cycles per instruction as measured on gfx950: a SIMD with one or two waves issues one
 // instruction per wave every 5.2 cycles (so two waves cost what one costs), three waves 8.3 in total,
-// four or more 2.45 each.  Fitted on 20 k - 1 M rows at dim 32 / 64 / 128; within 10 % of the
-// measured times except where the next smaller layout is equally fast.
-double layout_cost(int64_t rows, int32_t elems, int32_t lanes, int32_t n_iter, bool row_per_lane)
+// four or more 2.45 each.  Every kernel runs in four-wave workgroups, whose waves land one on each SIMD of a compute
+// unit, so a SIMD holds the average number of waves rounded up.  Fitted on 1 k - 1 M rows at dim 32 / 64 / 128; within
+// 10 % of the measured times (plus some 10 us of launch and first load that every layout pays) except where the next
+// smaller layout is equally fast.
+// `twin`: two groups of `lanes` lanes per row score the two ranges of a trip at the same time: a wave holds half as many
+// rows and its chain is 1 + n_iter ranges long instead of 1 + 2 * n_iter (and three instructions per trip to swap sums).
+double layout_cost(int64_t rows, int32_t elems, int32_t lanes, int32_t n_iter, bool row_per_lane, bool twin = false)
 {
     int steps = 0;
     while ((1 << steps) < lanes) ++steps;
@@ -95,12 +107,15 @@ double layout_cost(int64_t rows, int32_t elems, int32_t lanes, int32_t n_iter, b
     // the result round, each worth some 14 instructions with its select and addition) instead of DPP moves
     const bool pow2 = (lanes & (lanes - 1)) == 0;
     const double per_range = 8.0 * elems + 30.0 + (pow2 ? 6.0 * steps : 14.0 * (steps + 1));
-    const double instructions = (1.0 + 2.0 * n_iter) * per_range + 10.0 * elems;
-    const int64_t rows_per_block = row_per_lane ? 64 : 4 * (64 / lanes);
-    const int64_t waves = (rows + rows_per_block - 1) / rows_per_block * (row_per_lane ? 1 : 4);
+    const double instructions = twin ? (1.0 + n_iter) * per_range + 3.0 * n_iter + 10.0 * elems
+                                     : (1.0 + 2.0 * n_iter) * per_range + 10.0 * elems;
+    const int64_t rows_per_wave = row_per_lane ? 64 : 64 / (twin ? 2 * lanes : lanes);
+    const int64_t waves = (rows + rows_per_wave - 1) / rows_per_wave;
     const int64_t per_simd = (waves + 1023) / 1024;
     const double cycles_per_instruction = per_simd <= 2 ? 5.2 : per_simd == 3 ? 8.3 : 2.45 * (double)per_simd;
-    return instructions * cycles_per_instruction;
+    // measured, two groups per row gain less than their instruction count says (every row is loaded twice, and a
+    // launch has some 10 us that no layout shortens): a tenth is added so that a near tie goes to the plain layout
+    return instructions * cycles_per_instruction * (twin ? 1.1 : 1.0);
 }
 
 int enqueue_greedy(const void* table, int dtype, int64_t rows, int32_t dim, int64_t row_stride, int32_t nbits,
@@ -130,11 +145,13 @@ int enqueue_greedy(const void* table, int dtype, int64_t rows, int32_t dim, int6
     // see layout_cost.  ratio == 0 is bound by HBM and always takes E = 8 (a wave then reads and
     // writes contiguous memory).
     int E = 0, L = 1;  // E == 0: one row per lane
+    bool twin = false;
     const int64_t forced = g_greedy_layout.load(std::memory_order_relaxed);
     if (forced == 1) {
         if (!(e4q::rpl_supports_dim(dim) || e4q::rpl_tail_supports_dim(dim))) return E4Q_ERR_BAD_OPTION;
     } else if (forced != 0) {
-        E = (int)(forced >> 8);
+        twin = (forced & kTwin) != 0;
+        E = (int)((forced & ~kTwin) >> 8);
         L = (int)(forced & 0xff);
         if ((int64_t)E * L < dim) return E4Q_ERR_BAD_OPTION;
     } else if (n_iter == 0) {
@@ -165,13 +182,27 @@ int enqueue_greedy(const void* table, int dtype, int64_t rows, int32_t dim, int6
                     best = c;
                     E = e;
                     L = l;
+                    twin = false;
+                }
+                // few rows: the same lanes twice, one group per candidate range of a trip
+                if (e <= 16 && l == l_pow2 && l <= 32) {
+                    const double ct = layout_cost(rows, e, l, n_iter, false, true);
+                    if (ct < best) {
+                        best = ct;
+                        E = e;
+                        L = l;
+                        twin = true;
+                    }
                 }
             }
         }
     }
-    g_greedy_layout_chosen.store(E == 0 ? 1 : ((int64_t)E << 8) | L, std::memory_order_relaxed);
+    g_greedy_layout_chosen.store(E == 0 ? 1 : (twin ? kTwin : 0) | ((int64_t)E << 8) | L, std::memory_order_relaxed);
     hipError_t err;
-    if (E == 0 && dim % 8 == 0 && dim > 128) {
+    if (twin) {
+        err = dtype == E4Q_F32 ? e4q::launch_greedy_swl_twin_f32(a, dim, E, L, stream)
+                               : e4q::launch_greedy_swl_twin_f16(a, dim, E, L, stream);
+    } else if (E == 0 && dim % 8 == 0 && dim > 128) {
         err = dtype == E4Q_F32 ? e4q::launch_greedy_rpl_wide_f32(a, dim, stream)
                                : e4q::launch_greedy_rpl_wide_f16(a, dim, stream);
     } else if (E == 0 && dim % 8 == 0) {
@@ -262,10 +293,13 @@ int e4q_quantize_rowwise_greedy_batch(const e4q_table_desc* descs, int32_t n_tab
                     members.push_back(u);
                     waves += (descs[u].rows + 63) / 64;
                 }
-            if (members.size() < 2 || waves < 512 || waves > 0x3ffffffLL) continue;  // 64 work-items each: below 2^32 per launch
+            if (members.size() < 2 || waves < 512 || waves > 0x3ffffffLL) continue;  // below 2^32 work-items per launch
             for (size_t first = 0; first < members.size(); first += e4q::kMaxGroupTables) {
                 e4q::GreedyGroup g;
                 g.n_tables = (int32_t)std::min<size_t>(e4q::kMaxGroupTables, members.size() - first);
+                int64_t rows_in_launch = 0;
+                for (int32_t k = 0; k < g.n_tables; ++k) rows_in_launch += descs[members[first + k]].rows;
+                g.rows_per_block = e4q::rpl_rows_per_block(rows_in_launch);
                 g.n_iter = n_iter;
                 g.n_bins = (float)n_bins;
                 g.nbits = nbits;
@@ -284,7 +318,7 @@ int e4q_quantize_rowwise_greedy_batch(const e4q_table_desc* descs, int32_t n_tab
                         e.bias_f16 = d.bias_f16;
                         e.vec_loads = (aligned(d.table, 16) && (d.row_stride * esz) % 16 == 0) ? 1u : 0u;
                         e.vec_stores = aligned(d.codes, 16) ? 2u : (aligned(d.codes, 4) ? 1u : 0u);
-                        blocks += (uint32_t)((d.rows + 63) / 64);
+                        blocks += (uint32_t)((d.rows + g.rows_per_block - 1) / g.rows_per_block);
                         done[members[first + k]] = 1;
                     } else {
                         g.tables[k] = e4q::GreedyTable{};
@@ -434,9 +468,9 @@ double e4q_greedy_layout_cost(int64_t rows, int32_t dim, int32_t n_iter, int64_t
         if (!(e4q::rpl_supports_dim(dim) || e4q::rpl_tail_supports_dim(dim))) return -1.0;
         return layout_cost(rows, (dim + 7) / 8 * 8, 1, n_iter, true);
     }
-    const int32_t e = (int32_t)(layout >> 8), l = (int32_t)(layout & 0xff);
+    const int32_t e = (int32_t)((layout & ~kTwin) >> 8), l = (int32_t)(layout & 0xff);
     if ((int64_t)e * l < dim) return -1.0;
-    return layout_cost(rows, e, l, n_iter, false);
+    return layout_cost(rows, e, l, n_iter, false, (layout & kTwin) != 0);
 }
 
 int e4q_set_option(const char* name, int64_t value)
@@ -472,6 +506,6 @@ const char* e4q_strerror(int code)
 
 const char* e4q_last_hip_error(void) { return g_hip_error; }
 
-int e4q_version(void) { return 310; }  // 0.3.1
+int e4q_version(void) { return 400; }  // 0.4.0
 
 }  // extern "C"

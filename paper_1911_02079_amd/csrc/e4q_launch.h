@@ -22,6 +22,12 @@ struct GreedyArgs {
     float qmax;           // 2^nbits - 1
 };
 
+// Rows (= work-items) per workgroup of the one-row-per-lane kernels: 256 (four waves, one on each SIMD of a compute
+// unit) while the launch has fewer than 8 waves per SIMD of the chip, 64 beyond (see greedy_rpl.h).  The kernels for
+// dimensions that are not multiples of 8 stage their codes in LDS per workgroup and always take 256.
+constexpr int kRplMaxRowsPerBlock = 256;
+inline int rpl_rows_per_block(int64_t rows_in_launch) { return rows_in_launch >= (int64_t)8 * 1024 * 64 ? 64 : kRplMaxRowsPerBlock; }
+
 // One launch over several tables of the same dimension and input type (one row per lane).
 constexpr int kMaxGroupTables = 16;
 struct GreedyTable {
@@ -35,12 +41,13 @@ struct GreedyTable {
     uint32_t vec_stores;
 };
 struct GreedyGroup {
+    int32_t rows_per_block;  // 64 or 256 (rpl_rows_per_block of the launch's rows): the workgroup size
     int32_t n_tables;  // 1 .. kMaxGroupTables
     int32_t n_iter;
     float n_bins;
     int32_t nbits;
     float qmax;
-    uint32_t block_end[kMaxGroupTables];  // running total of ceil(rows / 64) workgroups
+    uint32_t block_end[kMaxGroupTables];  // running total of ceil(rows / rows_per_block) workgroups
     GreedyTable tables[kMaxGroupTables];
 };
 
@@ -72,6 +79,9 @@ hipError_t launch_greedy_swl_f32_big(const GreedyArgs& a, int32_t dim, int E, in
 hipError_t launch_greedy_swl_f16_small(const GreedyArgs& a, int32_t dim, int E, int L, hipStream_t stream);
 hipError_t launch_greedy_swl_f16_mid(const GreedyArgs& a, int32_t dim, int E, int L, hipStream_t stream);
 hipError_t launch_greedy_swl_f16_big(const GreedyArgs& a, int32_t dim, int E, int L, hipStream_t stream);
+// Two groups of L lanes per row, one per candidate range of a trip: E in {8, 16}, L a power of two up to 32.
+hipError_t launch_greedy_swl_twin_f32(const GreedyArgs& a, int32_t dim, int E, int L, hipStream_t stream);
+hipError_t launch_greedy_swl_twin_f16(const GreedyArgs& a, int32_t dim, int E, int L, hipStream_t stream);
 // The same with any number of lanes per row from 2 to 64 (a wave holds 64 / lanes rows): E in {8 .. 128}.
 hipError_t launch_greedy_swl_any_f32(const GreedyArgs& a, int32_t dim, int E, int lanes, hipStream_t stream);
 hipError_t launch_greedy_swl_any_f16(const GreedyArgs& a, int32_t dim, int E, int lanes, hipStream_t stream);

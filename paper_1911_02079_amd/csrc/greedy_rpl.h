@@ -7,6 +7,12 @@
 // greedy decisions are all lane-local, and every lane does useful work in every instruction.
 // The loop trip count is the same for every row, so the wave never diverges.
 //
+// The waves of a workgroup share nothing.  A table of fewer than 8 waves per SIMD runs in four-wave workgroups, whose
+// waves are spread over the four SIMDs of a compute unit, which one-wave workgroups are not (measured: with one to
+// two waves per SIMD on average, or exactly four, tables of 100 000 - 260 000 rows ran 15 - 50 % longer in one-wave
+// workgroups); larger tables run in one-wave workgroups (the same speed within 0.5 %, a batch of 26 tables 1.5 % faster).
+// The kernels take the workgroup size from the launch.
+//
 // Memory access: lane l reads row (base + l) in 16-byte pieces; across the wave these are 64
 // different cache lines per instruction, which costs a few thousand cycles per wave once, against
 // some 150 000 cycles of arithmetic for D = 128 -- the kernel is bound by VALU issue, not by HBM.
@@ -19,7 +25,7 @@
 
 namespace e4q {
 
-constexpr int kRplBlock = 64;  // one wave per workgroup; no LDS, no barriers
+constexpr int kRplBlock = kRplMaxRowsPerBlock;  // largest workgroup: four independent waves; no LDS, no barriers
 
 template <int D>
 __device__ __forceinline__ void load_row(const float* __restrict__ row, bool vec, float (&x)[D])
@@ -156,29 +162,38 @@ __device__ __forceinline__ void greedy_rpl_row(const GreedyArgs& a, int64_t row,
     else encode(Idx<2>{});
 }
 
+// First row of the calling wave, given the first row of its workgroup.  A wave whose first row is beyond the table
+// (in the table's last workgroup) has nothing to do.
+__device__ __forceinline__ int64_t rpl_wave_first_row(int64_t block_first_row)
+{
+    return block_first_row + (int64_t)(threadIdx.x & ~63u);
+}
+
 template <int D, typename Tin>
 __global__ void __launch_bounds__(kRplBlock) greedy_rpl_kernel(GreedyArgs a)
 {
-    greedy_rpl_row<D, Tin>(a, (int64_t)blockIdx.x * kRplBlock + threadIdx.x);
+    const int64_t row0 = (int64_t)blockIdx.x * blockDim.x;  // 64 or 256 rows per workgroup, the launcher's choice
+    if (rpl_wave_first_row(row0) >= a.rows) return;  // no barrier in this kernel
+    greedy_rpl_row<D, Tin>(a, row0 + threadIdx.x);
 }
 
 // The same for a dimension d that is not a multiple of 8, D = d rounded up.
 // Rows of d * nbits / 8 bytes are not multiples of 4 bytes long, so a lane cannot store its row in
-// words; the wave's 64 rows are contiguous in memory, though, and start at a multiple of 64 bytes.
-// Each lane packs its row into LDS (8 KiB, an image of those 64 rows) and the wave copies the image out
-// 16 bytes per lane at a time.
+// words; the workgroup's 256 rows are contiguous in memory, though, and start at a multiple of 256 bytes.
+// Each lane packs its row into LDS (an image of those 256 rows, D bytes each) and the workgroup copies the
+// image out 16 bytes per lane at a time.
 template <int D, typename Tin>
 __global__ void __launch_bounds__(kRplBlock) greedy_rpl_tail_kernel(GreedyArgs a, int32_t d)
 {
     __shared__ __attribute__((aligned(16))) uint8_t stage[kRplBlock * D];  // D bytes per row cover 8-bit codes
     const int64_t row0 = (int64_t)blockIdx.x * kRplBlock;
-    greedy_rpl_row<D, Tin, true>(a, row0 + threadIdx.x, d, stage);
+    if (rpl_wave_first_row(row0) < a.rows) greedy_rpl_row<D, Tin, true>(a, row0 + threadIdx.x, d, stage);  // wave-uniform
     __syncthreads();
     const int nbytes = (d * a.nbits + 7) / 8;
     const int64_t rows_here = a.rows - row0 < kRplBlock ? a.rows - row0 : kRplBlock;
     const int total = (int)rows_here * nbytes;
     uint8_t* dst = a.codes + row0 * nbytes;
-    if (a.vec_stores == 2) {  // 16-byte aligned buffer: 64 * nbytes keeps every wave's start aligned
+    if (a.vec_stores == 2) {  // 16-byte aligned buffer: 256 * nbytes keeps every workgroup's start aligned
         for (int off = (int)threadIdx.x * 16; off < total; off += kRplBlock * 16) {
             if (off + 16 <= total) {
                 *reinterpret_cast<uint4*>(dst + off) = *reinterpret_cast<const uint4*>(stage + off);
@@ -191,8 +206,8 @@ __global__ void __launch_bounds__(kRplBlock) greedy_rpl_tail_kernel(GreedyArgs a
     }
 }
 
-// Several tables of one dimension and input type in one launch: workgroup b belongs to the first
-// table whose block_end exceeds b.  Small tables then share the chip with large ones instead of
+// Several tables of one dimension and input type in one launch (a table takes ceil(rows / rows_per_block) workgroups):
+// workgroup b belongs to the first table whose block_end exceeds b.  Small tables then share the chip with large ones instead of
 // each waiting for a launch of its own to drain.
 template <int D, typename Tin>
 __global__ void __launch_bounds__(kRplBlock) greedy_rpl_group_kernel(GreedyGroup g)
@@ -214,24 +229,28 @@ __global__ void __launch_bounds__(kRplBlock) greedy_rpl_group_kernel(GreedyGroup
     a.bias_f16 = e.bias_f16;
     a.vec_loads = e.vec_loads;
     a.vec_stores = e.vec_stores;
-    greedy_rpl_row<D, Tin>(a, (int64_t)(blockIdx.x - first_block) * kRplBlock + threadIdx.x);
+    const int64_t row0 = (int64_t)(blockIdx.x - first_block) * blockDim.x;
+    if (rpl_wave_first_row(row0) >= a.rows) return;  // no barrier in this kernel
+    greedy_rpl_row<D, Tin>(a, row0 + threadIdx.x);
 }
 
 template <int D, typename Tin>
 inline hipError_t launch_greedy_rpl_group(const GreedyGroup& g, hipStream_t stream)
 {
     const uint32_t blocks = g.block_end[g.n_tables - 1];
-    hipLaunchKernelGGL((greedy_rpl_group_kernel<D, Tin>), dim3(blocks), dim3(kRplBlock), 0, stream, g);
+    if (g.rows_per_block != 64 && g.rows_per_block != kRplBlock) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((greedy_rpl_group_kernel<D, Tin>), dim3(blocks), dim3((unsigned)g.rows_per_block), 0, stream, g);
     return hipGetLastError();
 }
 
-// Host-side launcher for one (D, Tin) instantiation.  One 64-thread workgroup per 64 rows: the grid has
-// as many work-items as the table has rows (rounded up), at most 2^31 + 63, which one grid dimension holds.
+// Host-side launcher for one (D, Tin) instantiation.  One work-item per row (rounded up to whole workgroups of 64 or
+// 256), at most 2^31 + 255, which one grid dimension holds.
 template <int D, typename Tin>
 inline hipError_t launch_greedy_rpl(const GreedyArgs& a, hipStream_t stream)
 {
-    const int64_t blocks = (a.rows + kRplBlock - 1) / kRplBlock;
-    hipLaunchKernelGGL((greedy_rpl_kernel<D, Tin>), dim3((unsigned)blocks), dim3(kRplBlock), 0, stream, a);
+    const int64_t block = rpl_rows_per_block(a.rows);
+    const int64_t blocks = (a.rows + block - 1) / block;
+    hipLaunchKernelGGL((greedy_rpl_kernel<D, Tin>), dim3((unsigned)blocks), dim3((unsigned)block), 0, stream, a);
     return hipGetLastError();
 }
 

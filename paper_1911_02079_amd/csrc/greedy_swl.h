@@ -129,21 +129,31 @@ __device__ __forceinline__ float swl_range_loss(const float (&x)[E], const float
 
 // L = 0: `lanes` lanes per row, a run-time number that need not be a power of two; a wave then holds
 // 64 / lanes rows and its last 64 % lanes lanes idle (they redo a row and store nothing).
-template <int E, int L, typename Tin, int MASK>
+//
+// TWIN (L a power of two up to 32): a row has two groups of L lanes, each holding the whole row, and the two
+// ranges that Algorithm 1 scores per trip are scored at the same time, the left candidate by the first group and the
+// right one by the second; the groups swap their sums and take the same decision.  The arithmetic per row is the
+// same (plus one load and one first range), the chain of dependent trips is half as long: for tables too small
+// to give every SIMD two waves, where the duration of the kernel is the duration of one wave.
+template <int E, int L, typename Tin, int MASK, bool TWIN = false>
 __global__ void __launch_bounds__(kSwlBlock) greedy_swl_kernel(GreedyArgs a, int32_t d, int32_t lanes_rt)
 {
     constexpr bool MASKED = MASK != 0;
     static_assert(E % 8 == 0 && (E & (E - 1)) == 0 && (L & (L - 1)) == 0 && L <= 64, "bad layout");
+    static_assert(!TWIN || (L >= 1 && L <= 32), "two groups of L lanes must fit a wave");
     const int lanes = L != 0 ? L : lanes_rt;
     int sub;
     int64_t row0, row;
     bool live;
+    bool second = false;  // TWIN: this lane belongs to the group that scores the right candidate
     if constexpr (L != 0) {
-        constexpr int kRowsPerBlock = kSwlBlock / L;
+        constexpr int kGroup = TWIN ? 2 * L : L;
+        constexpr int kRowsPerBlock = kSwlBlock / kGroup;
         sub = threadIdx.x % L;
         row0 = linear_block() * kRowsPerBlock;
-        row = row0 + threadIdx.x / L;
+        row = row0 + threadIdx.x / kGroup;
         live = true;
+        if constexpr (TWIN) second = ((threadIdx.x / L) & 1u) != 0;
     } else {
         const int rows_per_wave = 64 / lanes;
         const int lane = (int)(threadIdx.x & 63u), wave = (int)(threadIdx.x >> 6);
@@ -213,8 +223,17 @@ __global__ void __launch_bounds__(kSwlBlock) greedy_swl_kernel(GreedyArgs a, int
         for (int it = 0; it < a.n_iter; ++it) {
             const float next_lo = cur_lo + stepsize;
             const float next_hi = cur_hi - stepsize;
-            const float loss_l = swl_range_loss<E, L, MASK>(x, keep, nvalid, next_lo, cur_hi, a.qmax, sub, lanes);
-            const float loss_r = swl_range_loss<E, L, MASK>(x, keep, nvalid, cur_lo, next_hi, a.qmax, sub, lanes);
+            float loss_l, loss_r;
+            if constexpr (TWIN) {
+                const float mine = swl_range_loss<E, L, MASK>(x, keep, nvalid, second ? cur_lo : next_lo,
+                                                              second ? next_hi : cur_hi, a.qmax, sub, lanes);
+                const float theirs = lane_xor<L>(mine);  // the other group's lane at the same position
+                loss_l = second ? theirs : mine;
+                loss_r = second ? mine : theirs;
+            } else {
+                loss_l = swl_range_loss<E, L, MASK>(x, keep, nvalid, next_lo, cur_hi, a.qmax, sub, lanes);
+                loss_r = swl_range_loss<E, L, MASK>(x, keep, nvalid, cur_lo, next_hi, a.qmax, sub, lanes);
+            }
             const bool left = loss_l < loss_r;  // a tie moves the upper bound
             cur_lo = left ? next_lo : cur_lo;
             cur_hi = left ? cur_hi : next_hi;
@@ -230,6 +249,7 @@ __global__ void __launch_bounds__(kSwlBlock) greedy_swl_kernel(GreedyArgs a, int
     const uint16_t scale_bits = f16_bits(scale32);
     const uint16_t bias_bits = f16_bits(best_lo);
     const StoredParams p = params_from_bits(scale_bits, bias_bits, a.qmax);
+    if constexpr (TWIN) live = live && !second;  // both groups hold the result; the first one stores it
     if (live && sub == 0) {
         a.scale_f16[row] = scale_bits;
         a.bias_f16[row] = bias_bits;
@@ -258,6 +278,16 @@ inline hipError_t launch_greedy_swl(const GreedyArgs& a, int32_t d, hipStream_t 
     return hipGetLastError();
 }
 
+// Two groups of L lanes per row (see TWIN above).
+template <int E, int L, typename Tin, int MASK>
+inline hipError_t launch_greedy_swl_twin(const GreedyArgs& a, int32_t d, hipStream_t stream)
+{
+    constexpr int kRowsPerBlock = kSwlBlock / (2 * L);
+    const int64_t blocks = (a.rows + kRowsPerBlock - 1) / kRowsPerBlock;
+    hipLaunchKernelGGL((greedy_swl_kernel<E, L, Tin, MASK, true>), grid_for(blocks), dim3(kSwlBlock), 0, stream, a, d, L);
+    return hipGetLastError();
+}
+
 // `lanes` lanes per row, 2 .. 64, not necessarily a power of two.
 template <int E, typename Tin, int MASK>
 inline hipError_t launch_greedy_swl_any(const GreedyArgs& a, int32_t d, int32_t lanes, hipStream_t stream)
@@ -277,6 +307,7 @@ template <typename Tin>
 hipError_t dispatch_greedy_swl(const GreedyArgs& a, int32_t d, int E, int L, hipStream_t stream)
 {
     const int mask = (d == E * L) ? 0 : (d % 8 == 0 ? 1 : 2);
+    (void)mask;  // a translation unit may list no layout
 #define E4Q_SWL(EE, LL)                                                              \
     if (E == EE && L == LL) {                                                        \
         if (mask == 0) return launch_greedy_swl<EE, LL, Tin, 0>(a, d, stream);       \
@@ -287,6 +318,24 @@ hipError_t dispatch_greedy_swl(const GreedyArgs& a, int32_t d, int E, int L, hip
 #undef E4Q_SWL
     return hipErrorInvalidValue;
 }
+
+// The same for the layouts with two groups per row that the translation unit lists in E4Q_SWL_TWIN_LAYOUTS.
+#ifdef E4Q_SWL_TWIN_LAYOUTS
+template <typename Tin>
+hipError_t dispatch_greedy_swl_twin(const GreedyArgs& a, int32_t d, int E, int L, hipStream_t stream)
+{
+    const int mask = (d == E * L) ? 0 : (d % 8 == 0 ? 1 : 2);
+#define E4Q_SWL_TWIN(EE, LL)                                                            \
+    if (E == EE && L == LL) {                                                           \
+        if (mask == 0) return launch_greedy_swl_twin<EE, LL, Tin, 0>(a, d, stream);     \
+        if (mask == 1) return launch_greedy_swl_twin<EE, LL, Tin, 1>(a, d, stream);     \
+        return launch_greedy_swl_twin<EE, LL, Tin, 2>(a, d, stream);                    \
+    }
+    E4Q_SWL_TWIN_LAYOUTS
+#undef E4Q_SWL_TWIN
+    return hipErrorInvalidValue;
+}
+#endif
 
 // The same for a lane count that is not a power of two: E from the list in E4Q_SWL_ANY_E.
 template <typename Tin>

@@ -172,7 +172,9 @@ def test_diagnostic_options(lib):
     assert lib.e4q_set_option(None, 1) == -8
     assert lib.e4q_set_option(b"kmeans_force_scan", 2) == -8
     assert lib.e4q_set_option(b"sls_nontemporal", -1) == -8
-    for bad in [(8 << 8) | 65, (8 << 8) | 128, (12 << 8) | 4, (128 << 8) | 64, (8 << 8), 2, -1]:
+    twin = 1 << 16  # two groups of L lanes per row: E in {8, 16}, L a power of two up to 32
+    for bad in [(8 << 8) | 65, (8 << 8) | 128, (12 << 8) | 4, (128 << 8) | 64, (8 << 8), 2, -1,
+                twin | (32 << 8) | 2, twin | (8 << 8) | 64, twin | (8 << 8) | 3, twin, twin | 1, (2 << 16) | (8 << 8) | 4]:
         assert lib.e4q_set_option(b"greedy_layout", bad) == -8
         assert lib.e4q_get_option(b"greedy_layout") == 0
     p = ctypes.c_void_p(0x1000)
@@ -182,6 +184,9 @@ def test_diagnostic_options(lib):
         assert lib.e4q_get_option(b"greedy_layout") == (8 << 8) | 4
         assert q(p, 0, 10, 64, 64, 4, 200, 0.16, p, p, p, None) == -8
         assert q(p, 0, 10, 64, 64, 3, 200, 0.16, p, p, p, None) == -3       # ordinary validation comes first
+        assert lib.e4q_set_option(b"greedy_layout", twin | (8 << 8) | 4) == 0
+        assert lib.e4q_get_option(b"greedy_layout") == twin | (8 << 8) | 4
+        assert q(p, 0, 10, 64, 64, 4, 200, 0.16, p, p, p, None) == -8       # two groups of 4 lanes x 8 hold 32, not 64
         assert lib.e4q_set_option(b"greedy_layout", 1) == 0                  # one row per lane: dim <= 224
         assert q(p, 0, 10, 256, 256, 4, 200, 0.16, p, p, p, None) == -8
         from paper_1911_02079_amd.binding import TableDesc
@@ -202,6 +207,10 @@ def test_diagnostic_options(lib):
     # a lane count that is not a power of two: 384 elements on 3 lanes beat 4 lanes of which one idles
     assert 0 < cost(10_000_000, 384, 32, (128 << 8) | 3) < cost(10_000_000, 384, 32, (128 << 8) | 4)
     assert cost(1000, 384, 32, (64 << 8) | 5) < 0
+    # few rows: a second group of lanes per row halves the chain of dependent trips; many rows: it only adds a range
+    assert 0 < cost(1000, 64, 32, twin | (8 << 8) | 8) < cost(1000, 64, 32, (8 << 8) | 8)
+    assert cost(1_000_000, 64, 32, twin | (8 << 8) | 8) > cost(1_000_000, 64, 32, (8 << 8) | 8)
+    assert cost(1000, 64, 32, twin | (8 << 8) | 4) < 0
     assert lib.e4q_set_option(b"kmeans_force_scan", 1) == 0 and lib.e4q_get_option(b"kmeans_force_scan") == 1
     assert lib.e4q_set_option(b"kmeans_force_scan", 0) == 0
 
@@ -219,6 +228,10 @@ def test_binding_checks_caller_supplied_outputs():
         binding._check_out(good, torch.uint8, (4, 32), torch.device("cpu"), "codes")  # not a GPU tensor
     assert binding.greedy_layout_value(None) == 0 and binding.greedy_layout_value("rpl") == 1
     assert binding.greedy_layout_value("64,2") == (64 << 8) | 2 and binding.greedy_layout_value((8, 16)) == (8 << 8) | 16
+    assert binding.greedy_layout_value("8,4,twin") == (1 << 16) | (8 << 8) | 4 == binding.greedy_layout_value((8, 4, True))
+    assert "2 groups" in binding.greedy_layout_name((1 << 16) | (8 << 8) | 4) and binding.greedy_layout_name(1) == "one row per lane"
+    with pytest.raises(ValueError):
+        binding.greedy_layout_value("8,4,5")
     del dev
 
 

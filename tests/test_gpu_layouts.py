@@ -31,7 +31,8 @@ def e4q():
 def layouts_for(dim):
     """One row per lane where it exists, then every compiled (E, L) with the smallest power of two L that
     holds the row, plus one with twice that many lanes (lanes beyond the row hold no element); and the lane
-    counts that are not powers of two: the smallest that holds the row, one more, and 3 where 2 would do."""
+    counts that are not powers of two: the smallest that holds the row, one more, and 3 where 2 would do; and the
+    layouts with two groups of lanes per row, (E, L, True), for E = 8 and 16."""
     out = ["rpl"] if dim <= 224 else []
     for e in (8, 16, 32, 64, 128):
         l = 1
@@ -42,6 +43,10 @@ def layouts_for(dim):
             out.append((e, l))
             if 2 * l <= lmax and e in (8, 32):
                 out.append((e, 2 * l))
+        if e <= 16 and l <= 32:  # two groups of l lanes per row, one per candidate range of a trip
+            out.append((e, l, True))
+            if 2 * l <= 32 and e == 8:
+                out.append((e, 2 * l, True))
         need = -(-dim // e)
         for lanes in sorted({need, need + 1, 3, 63}):
             if need <= lanes <= 64 and lanes & (lanes - 1) and (lanes <= need + 1 or e == 8):
@@ -50,7 +55,7 @@ def layouts_for(dim):
 
 
 @pytest.mark.parametrize("half", [False, True], ids=["f32", "f16"])
-@pytest.mark.parametrize("dim", [32, 64, 100, 128, 136, 150, 192, 199, 200, 223, 224, 250, 300, 320, 384, 768, 999, 1000, 1999, 3000])
+@pytest.mark.parametrize("dim", [1, 7, 8, 13, 16, 32, 64, 100, 128, 136, 150, 192, 199, 200, 223, 224, 250, 300, 320, 384, 768, 999, 1000, 1999, 3000])
 def test_every_forced_layout_matches_the_oracle(e4q, oracle_lib, dim, half):
     from paper_1911_02079_amd import synth
 
@@ -76,7 +81,7 @@ def test_forced_layout_applies_to_batches_and_plain_min_max(e4q, oracle_lib):
 
     tables = [synth.gaussian_table(700 + 13 * k, 64, 0.1, seed=800 + k, device="cuda") for k in range(4)]
     try:
-        for layout in ["rpl", (16, 4), (64, 1), (16, 5), (8, 11)]:
+        for layout in ["rpl", (16, 4), (64, 1), (16, 5), (8, 11), (8, 8, True), (16, 4, True)]:
             for n_bins, ratio in [(100, 0.16), (200, 0.0)]:
                 say(f"batch of 4 tables with forced layout {layout}, b={n_bins} r={ratio}")
                 e4q.set_option("greedy_layout", e4q.greedy_layout_value(layout))

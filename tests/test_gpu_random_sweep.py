@@ -98,7 +98,8 @@ def untouched(buf, span, fill):
 
 def layouts_for(dim):
     """Values of the `greedy_layout` option that can hold a row of `dim` elements: automatic (three times as likely),
-    one row per lane, and for every E the fewest lanes, one lane more, and the next power of two."""
+    one row per lane, for every E the fewest lanes, one lane more, and the next power of two, and for E = 8 and 16 the
+    layout with two groups of lanes per row."""
     out = [0, 0, 0]
     if dim <= 224:
         out.append(1)
@@ -113,6 +114,8 @@ def layouts_for(dim):
             if lanes > 64 or ((lanes & (lanes - 1)) == 0 and e == 128 and lanes > 32):
                 continue
             out.append((e << 8) | lanes)
+        if e <= 16 and p2 <= 32:
+            out.append((1 << 16) | (e << 8) | p2)  # two groups of p2 lanes, one per candidate range of a trip
     return out
 
 
@@ -133,7 +136,7 @@ def test_greedy_and_dequantize_random_cases(e4q, oracle_lib):
         sbuf, scale, sspan = guarded((rows,), torch.float16, 7.0, int(rng.integers(0, 2)))
         bbuf, bias, bspan = guarded((rows,), torch.float16, 7.0, int(rng.integers(0, 2)))
         say(f"random greedy {k}: {rows} x {dim} {'binary16' if half else 'binary32'} nbits={nbits} b={n_bins} r={ratio} "
-            f"layout={layout if layout < 2 else (layout >> 8, layout & 255)} {how} codes at +{cspan[0] - GUARD}")
+            f"layout={e4q.greedy_layout_name(layout)} {how} codes at +{cspan[0] - GUARD}")
         e4q.set_option("greedy_layout", layout)
         try:
             e4q.quantize_rowwise_greedy(table, n_bins, ratio, nbits=nbits, out=(codes, scale, bias))

@@ -29,7 +29,7 @@ constexpr int kRplMaxRowsPerBlock = 256;
 inline int rpl_rows_per_block(int64_t rows_in_launch) { return rows_in_launch >= (int64_t)8 * 1024 * 64 ? 64 : kRplMaxRowsPerBlock; }
 
 // One launch over several tables of the same dimension and input type (one row per lane).
-constexpr int kMaxGroupTables = 16;
+constexpr int kMaxGroupTables = 64;  // a power of two (the kernel bisects block_end); the group travels as a kernel argument, under 4 KiB
 struct GreedyTable {
     const void* table;
     int64_t rows;

@@ -212,8 +212,13 @@ __global__ void __launch_bounds__(kRplBlock) greedy_rpl_tail_kernel(GreedyArgs a
 template <int D, typename Tin>
 __global__ void __launch_bounds__(kRplBlock) greedy_rpl_group_kernel(GreedyGroup g)
 {
+    static_assert((kMaxGroupTables & (kMaxGroupTables - 1)) == 0 && sizeof(GreedyGroup) <= 4096, "see e4q_launch.h");
+    // t = number of tables that end at or before this workgroup: a bisection over the running totals (entries beyond
+    // the last table hold the grand total, which no workgroup number reaches).  Uniform: six scalar steps.
     int t = 0;
-    while (t + 1 < g.n_tables && blockIdx.x >= g.block_end[t]) ++t;  // uniform: at most 15 scalar steps
+#pragma unroll
+    for (int step = kMaxGroupTables / 2; step >= 1; step /= 2)
+        if (blockIdx.x >= g.block_end[t + step - 1]) t += step;
     const uint32_t first_block = t == 0 ? 0u : g.block_end[t - 1];
     const GreedyTable& e = g.tables[t];
     GreedyArgs a;

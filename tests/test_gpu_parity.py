@@ -102,14 +102,14 @@ def test_config4_batch_of_half_tables(e4q, oracle_lib):
 
 
 def test_batch_grouping(e4q, oracle_lib):
-    """More tables of one dimension than fit one grouped launch (16), mixed with other dimensions,
-    input types, an empty table and a table too odd to group."""
+    """More tables of one dimension than fit one grouped launch (64; 150 make two full launches and a part), mixed
+    with other dimensions, input types, an empty table and a table too odd to group."""
     from paper_1911_02079_amd import synth
 
     rng = np.random.default_rng(0)
     tables = []
-    for k in range(40):
-        tables.append(synth.gaussian_table(int(rng.integers(100, 3000)), 64, 0.1, seed=9000 + k, device="cuda"))
+    for k in range(150):
+        tables.append(synth.gaussian_table(int(rng.integers(1, 3000)), 64, 0.1, seed=9000 + k, device="cuda"))
     for k in range(5):
         tables.append(synth.gaussian_table(int(rng.integers(5000, 30000)), 32, 0.1, seed=9100 + k, device="cuda",
                                            dtype=torch.float16))

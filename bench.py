@@ -266,6 +266,9 @@ def main() -> int:
                     help="thread layout of the greedy search: auto (the library's cost model), rpl (one row per "
                          "lane), E,L (L lanes per row, E elements each) or E,L,twin (two such groups per row, one per candidate "
                          "range of a trip), through the greedy_layout diagnostic option")
+    ap.add_argument("--workgroup-waves", type=int, default=0, choices=[0, 1, 4],
+                    help="waves per workgroup of the row-per-lane kernels (greedy search, 16-means), through the "
+                         "workgroup_waves diagnostic option; 0: the library chooses by the row count")
     ap.add_argument("--row-pitch", type=int, default=0,
                     help="lookup workload: bytes between fused records (default: the smallest record, d/2 + 4)")
     ap.add_argument("--sls-nontemporal", action="store_true", help="lookup workload: non-temporal record gathers")
@@ -290,6 +293,7 @@ def main() -> int:
     e4q.binding.load_library()
     torch.cuda.set_device(0)
     e4q.set_option("greedy_layout", e4q.greedy_layout_value(args.layout))
+    e4q.set_option("workgroup_waves", args.workgroup_waves)
     e4q.set_option("sls_nontemporal", 1 if args.sls_nontemporal else 0)
     method, gen, rows, dim, params = WORKLOADS[args.workload]
     if method == "sls":
@@ -324,7 +328,7 @@ def main() -> int:
         out_bytes_per_row = e4q.packed_bytes(dim, nbits) + 4
         model_cycles = e4q.greedy_layout_cost(rows, dim, n_iter, chosen) if n_iter > 0 else None
         config = {"n_bins": n_bins, "ratio": ratio, "candidate_ranges_per_row": 1 + 2 * n_iter, "nbits": nbits,
-                  "layout": layout, "layout_forced": args.layout != "auto",
+                  "layout": layout, "layout_forced": args.layout != "auto", "workgroup_waves": args.workgroup_waves or "auto",
                   "layout_model_us": None if model_cycles is None else model_cycles / 2.4e3,
                   "step": "quantize_rowwise_greedy + dequantize, table resident in HBM"}
         metric = f"rows quantized/sec (greedy {nbits}-bit)"

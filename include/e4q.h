@@ -231,6 +231,11 @@ int32_t e4q_greedy_iterations(int32_t n_bins, float ratio);
  *                        instead of bisecting (the path otherwise taken only by rows whose centres
  *                        fall out of order).
  *   "sls_nontemporal"    1: e4q_sparse_lengths_sum_fused gathers records with non-temporal loads.
+ *   "workgroup_waves"    1 or 4: waves per workgroup of the kernels that give every table row a lane of its own (the
+ *                        greedy search in the one-row-per-lane layout, single tables and grouped batch launches, and
+ *                        the register-resident 16-means kernels); 0: the library chooses by the number of rows (four
+ *                        for small launches, whose waves then land one on each SIMD of a compute unit).  Kernels
+ *                        that stage rows in LDS per workgroup keep their own size.
  *   "greedy_layout_chosen"  read-only (e4q_get_option): the layout the last table handed to a
  *                        single-table greedy launch ran with, in the encoding of "greedy_layout"
  *                        (0 before the first such launch); grouped batch launches, which are

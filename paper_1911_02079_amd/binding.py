@@ -133,7 +133,7 @@ def greedy_iterations(n_bins: int, ratio: float) -> int:
 
 
 def set_option(name: str, value: int) -> None:
-    """e4q_set_option: a process-wide diagnostic switch ("greedy_layout", "kmeans_force_scan",
+    """e4q_set_option: a process-wide diagnostic switch ("greedy_layout", "workgroup_waves", "kmeans_force_scan",
     "sls_nontemporal"); see include/e4q.h."""
     _check(int(load_library().e4q_set_option(name.encode(), int(value))))
 

@@ -28,6 +28,7 @@ int fail_launch(hipError_t err)
 std::atomic<int64_t> g_greedy_layout{0};
 constexpr int64_t kTwin = (int64_t)1 << 16;
 std::atomic<int64_t> g_kmeans_force_scan{0};  // 1: scan all 16 centres instead of bisecting
+std::atomic<int64_t> g_workgroup_waves{0};    // 1 or 4: waves per workgroup of the row-per-lane kernels; 0: by row count
 std::atomic<int64_t> g_sls_nontemporal{0};    // 1: gather records with non-temporal loads
 std::atomic<int64_t> g_greedy_layout_chosen{0};  // read-only: layout of the last single-table greedy launch
 
@@ -36,6 +37,7 @@ std::atomic<int64_t>* find_option(const char* name)
     if (!name) return nullptr;
     if (std::strcmp(name, "greedy_layout") == 0) return &g_greedy_layout;
     if (std::strcmp(name, "kmeans_force_scan") == 0) return &g_kmeans_force_scan;
+    if (std::strcmp(name, "workgroup_waves") == 0) return &g_workgroup_waves;
     if (std::strcmp(name, "sls_nontemporal") == 0) return &g_sls_nontemporal;
     if (std::strcmp(name, "greedy_layout_chosen") == 0) return &g_greedy_layout_chosen;
     return nullptr;
@@ -137,6 +139,7 @@ int enqueue_greedy(const void* table, int dtype, int64_t rows, int32_t dim, int6
     a.vec_stores = aligned(codes, 16) ? 2u : (aligned(codes, 4) ? 1u : 0u);
     a.nbits = nbits;
     a.qmax = (float)((1 << nbits) - 1);
+    a.rpl_waves = (uint32_t)g_workgroup_waves.load(std::memory_order_relaxed);
 
     // Kernel choice.  One row per lane (rows/64 waves, the row in registers, ~3 % overhead over the
     // algorithmic operation count) does the arithmetic with the fewest instructions; a row spread over
@@ -302,7 +305,7 @@ int e4q_quantize_rowwise_greedy_batch(const e4q_table_desc* descs, int32_t n_tab
                 g.n_tables = (int32_t)std::min<size_t>(e4q::kMaxGroupTables, members.size() - first);
                 int64_t rows_in_launch = 0;
                 for (int32_t k = 0; k < g.n_tables; ++k) rows_in_launch += descs[members[first + k]].rows;
-                g.rows_per_block = e4q::rpl_rows_per_block(rows_in_launch);
+                g.rows_per_block = e4q::rpl_rows_per_block(rows_in_launch, (uint32_t)g_workgroup_waves.load(std::memory_order_relaxed));
                 g.n_iter = n_iter;
                 g.n_bins = (float)n_bins;
                 g.nbits = nbits;
@@ -382,6 +385,7 @@ int e4q_quantize_rowwise_kmeans16(const void* table, int dtype, int64_t rows, in
     a.vec_loads = (aligned(table, 16) && (row_stride * esz) % 16 == 0) ? 1u : 0u;
     a.vec_stores = aligned(idx, 16) ? 2u : (aligned(idx, 4) ? 1u : 0u);
     a.force_scan = g_kmeans_force_scan.load(std::memory_order_relaxed) != 0 ? 1u : 0u;
+    a.waves = (uint32_t)g_workgroup_waves.load(std::memory_order_relaxed);
     const hipError_t err = e4q::launch_kmeans16(a, dtype, dim, static_cast<hipStream_t>(hip_stream));
     return err == hipSuccess ? E4Q_OK : fail_launch(err);
 }
@@ -480,7 +484,10 @@ int e4q_set_option(const char* name, int64_t value)
 {
     std::atomic<int64_t>* opt = find_option(name);
     if (!opt || opt == &g_greedy_layout_chosen) return E4Q_ERR_BAD_OPTION;
-    if (opt == &g_greedy_layout ? !layout_value_ok(value) : (value != 0 && value != 1)) return E4Q_ERR_BAD_OPTION;
+    const bool ok = opt == &g_greedy_layout ? layout_value_ok(value)
+                    : opt == &g_workgroup_waves ? (value == 0 || value == 1 || value == 4)
+                                                : (value == 0 || value == 1);
+    if (!ok) return E4Q_ERR_BAD_OPTION;
     opt->store(value, std::memory_order_relaxed);
     return E4Q_OK;
 }

@@ -20,6 +20,7 @@ struct GreedyArgs {
     uint32_t vec_stores;  // 0: byte stores, 1: codes base 4-byte aligned, 2: 16-byte aligned
     int32_t nbits;        // 2, 4 or 8
     float qmax;           // 2^nbits - 1
+    uint32_t rpl_waves;   // one-row-per-lane kernels: waves per workgroup, 1 or 4; 0: chosen from the row count
 };
 
 // Rows (= work-items) per workgroup of the one-row-per-lane kernels: 256 (four waves, one on each SIMD of a compute
@@ -27,6 +28,11 @@ struct GreedyArgs {
 // dimensions that are not multiples of 8 stage their codes in LDS per workgroup and always take 256.
 constexpr int kRplMaxRowsPerBlock = 256;
 inline int rpl_rows_per_block(int64_t rows_in_launch) { return rows_in_launch >= (int64_t)8 * 1024 * 64 ? 64 : kRplMaxRowsPerBlock; }
+// The same with the diagnostic override (waves per workgroup, 0 = none).
+inline int rpl_rows_per_block(int64_t rows_in_launch, uint32_t forced_waves)
+{
+    return forced_waves == 1 ? 64 : forced_waves == 4 ? kRplMaxRowsPerBlock : rpl_rows_per_block(rows_in_launch);
+}
 
 // One launch over several tables of the same dimension and input type (one row per lane).
 constexpr int kMaxGroupTables = 64;  // a power of two (the kernel bisects block_end); the group travels as a kernel argument, under 4 KiB
@@ -97,6 +103,7 @@ struct KMeansArgs {
     uint32_t vec_loads;   // 1: table base and row pitch are 16-byte aligned
     uint32_t vec_stores;  // >= 1: idx base is 4-byte aligned; 2: 16-byte aligned
     uint32_t force_scan;  // 1: always scan all 16 centres (diagnostic; results are identical)
+    uint32_t waves;       // register-resident kernels: waves per workgroup, 1 or 4; 0: chosen from the row count
 };
 hipError_t launch_kmeans16(const KMeansArgs& a, int dtype, int32_t dim, hipStream_t stream);
 hipError_t launch_dequantize_codebook(const uint8_t* idx, const uint16_t* centroids_f16, int64_t rows,

@@ -234,6 +234,7 @@ __global__ void __launch_bounds__(kRplBlock) greedy_rpl_group_kernel(GreedyGroup
     a.bias_f16 = e.bias_f16;
     a.vec_loads = e.vec_loads;
     a.vec_stores = e.vec_stores;
+    a.rpl_waves = 0u;  // host-side field
     const int64_t row0 = (int64_t)(blockIdx.x - first_block) * blockDim.x;
     if (rpl_wave_first_row(row0) >= a.rows) return;  // no barrier in this kernel
     greedy_rpl_row<D, Tin>(a, row0 + threadIdx.x);
@@ -253,7 +254,7 @@ inline hipError_t launch_greedy_rpl_group(const GreedyGroup& g, hipStream_t stre
 template <int D, typename Tin>
 inline hipError_t launch_greedy_rpl(const GreedyArgs& a, hipStream_t stream)
 {
-    const int64_t block = rpl_rows_per_block(a.rows);
+    const int64_t block = rpl_rows_per_block(a.rows, a.rpl_waves);
     const int64_t blocks = (a.rows + block - 1) / block;
     hipLaunchKernelGGL((greedy_rpl_kernel<D, Tin>), dim3((unsigned)blocks), dim3((unsigned)block), 0, stream, a);
     return hipGetLastError();

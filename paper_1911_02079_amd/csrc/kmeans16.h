@@ -460,13 +460,16 @@ __global__ void __launch_bounds__(64 * WAVES) kmeans16_rpl_tail_kernel(KMeansArg
 }
 
 // Waves per workgroup for a table of `rows` rows (see kmeans16_rpl_body).
-inline int kmeans16_waves_per_block(int64_t rows) { return rows <= (int64_t)2 * 1024 * 64 ? 4 : 1; }
+inline int kmeans16_waves_per_block(const KMeansArgs& a)
+{
+    return a.waves == 1 || a.waves == 4 ? (int)a.waves : (a.rows <= (int64_t)2 * 1024 * 64 ? 4 : 1);
+}
 
 // Launches the register-resident kernel for `dim` if there is one; returns false otherwise.
 template <typename Tin>
 inline bool launch_kmeans16_rpl(const KMeansArgs& a, int32_t dim, hipStream_t stream)
 {
-    const int waves = kmeans16_waves_per_block(a.rows);
+    const int waves = kmeans16_waves_per_block(a);
     const dim3 grid((unsigned)((a.rows + 64 * waves - 1) / (64 * waves))), block(64 * waves);
     switch (dim) {
 #define E4Q_CASE(D) \
@@ -487,7 +490,7 @@ template <typename Tin>
 inline bool launch_kmeans16_rpl_tail(const KMeansArgs& a, int32_t dim, hipStream_t stream)
 {
     if (dim <= kK || dim >= 128 || dim % 8 == 0) return false;
-    const int waves = kmeans16_waves_per_block(a.rows);
+    const int waves = kmeans16_waves_per_block(a);
     const dim3 grid((unsigned)((a.rows + 64 * waves - 1) / (64 * waves))), block(64 * waves);
     switch ((dim + 7) / 8 * 8) {
 #define E4Q_CASE(D) \

@@ -165,13 +165,17 @@ def test_diagnostic_options(lib):
     lib.e4q_set_option.argtypes = [ctypes.c_char_p, ctypes.c_int64]
     lib.e4q_get_option.argtypes = [ctypes.c_char_p]
     lib.e4q_get_option.restype = ctypes.c_int64
-    for name in (b"greedy_layout", b"kmeans_force_scan", b"sls_nontemporal"):
+    for name in (b"greedy_layout", b"kmeans_force_scan", b"sls_nontemporal", b"workgroup_waves"):
         assert lib.e4q_get_option(name) == 0
     assert lib.e4q_set_option(b"no_such_option", 1) == -8
     assert lib.e4q_get_option(b"no_such_option") == -8
     assert lib.e4q_set_option(None, 1) == -8
     assert lib.e4q_set_option(b"kmeans_force_scan", 2) == -8
     assert lib.e4q_set_option(b"sls_nontemporal", -1) == -8
+    for bad in (2, 3, 8, -1):
+        assert lib.e4q_set_option(b"workgroup_waves", bad) == -8
+    for good in (1, 4, 0):
+        assert lib.e4q_set_option(b"workgroup_waves", good) == 0 and lib.e4q_get_option(b"workgroup_waves") == good
     twin = 1 << 16  # two groups of L lanes per row: E in {8, 16}, L a power of two up to 32
     for bad in [(8 << 8) | 65, (8 << 8) | 128, (12 << 8) | 4, (128 << 8) | 64, (8 << 8), 2, -1,
                 twin | (32 << 8) | 2, twin | (8 << 8) | 64, twin | (8 << 8) | 3, twin, twin | 1, (2 << 16) | (8 << 8) | 4]:

@@ -104,3 +104,43 @@ def test_a_layout_too_small_for_the_row_is_refused(e4q):
         assert err.value.code == -8
     finally:
         e4q.set_option("greedy_layout", 0)
+
+
+@pytest.mark.parametrize("waves", [1, 4])
+def test_forced_workgroup_sizes_match_the_oracle(e4q, oracle_lib, waves):
+    """The kernels that give a row a lane of its own run in one-wave or four-wave workgroups, normally chosen from the
+    row count; both sizes, forced through the "workgroup_waves" option, on row counts around whole workgroups: the
+    greedy search (single table, dimension with and without a masked tail, and a grouped batch) and 16-means."""
+    from helpers import oracle_kmeans_in_parallel
+    from paper_1911_02079_amd import synth
+
+    try:
+        e4q.set_option("workgroup_waves", waves)
+        e4q.set_option("greedy_layout", 1)
+        for rows, dim in [(1, 64), (63, 64), (64, 32), (65, 128), (255, 64), (256, 64), (257, 200), (1000, 100), (4099, 64)]:
+            say(f"{waves} wave(s) per workgroup: greedy {rows} x {dim}")
+            table = synth.outlier_table(rows, dim, seed=600 + rows + dim, device="cuda")
+            codes, scale, bias = e4q.quantize_rowwise_greedy(table, 100, 0.16)
+            torch.cuda.synchronize()
+            want = oracle_lib.quantize_rowwise_greedy(table.cpu().numpy(), 100, 0.16)
+            assert np.array_equal(codes.cpu().numpy(), want[0]) and np.array_equal(f16_bits(scale), want[1]) and \
+                np.array_equal(f16_bits(bias), want[2]), (rows, dim)
+        e4q.set_option("greedy_layout", 0)
+        tables = [synth.gaussian_table(r, 64, 0.1, seed=650 + r, device="cuda") for r in (1, 64, 65, 255, 256, 257, 700, 3000)]
+        say(f"{waves} wave(s) per workgroup: batch of {len(tables)} tables")
+        outs = e4q.quantize_rowwise_greedy_batch(tables, 100, 0.16)
+        torch.cuda.synchronize()
+        for t, (codes, scale, bias) in zip(tables, outs):
+            want = oracle_lib.quantize_rowwise_greedy(t.cpu().numpy(), 100, 0.16)
+            assert np.array_equal(codes.cpu().numpy(), want[0]) and np.array_equal(f16_bits(scale), want[1]) and \
+                np.array_equal(f16_bits(bias), want[2]), tuple(t.shape)
+        for rows, dim in [(1, 64), (64, 64), (65, 40), (255, 64), (257, 100), (1500, 64)]:
+            say(f"{waves} wave(s) per workgroup: 16-means {rows} x {dim}")
+            table = synth.mixture_table(rows, dim, seed=700 + rows, device="cuda")
+            idx, cen = e4q.quantize_rowwise_kmeans16(table, 5)
+            torch.cuda.synchronize()
+            w_idx, w_cen = oracle_kmeans_in_parallel(oracle_lib, table.cpu().numpy(), 5)
+            assert np.array_equal(idx.cpu().numpy(), w_idx) and np.array_equal(f16_bits(cen), w_cen), (rows, dim)
+    finally:
+        e4q.set_option("workgroup_waves", 0)
+        e4q.set_option("greedy_layout", 0)

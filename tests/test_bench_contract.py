@@ -59,3 +59,21 @@ def test_json_line(args, kernel):
     assert any(kernel in name for name in d["kernels"])
     cb = d["cpu_baseline"]
     assert cb["kind"] == "oracle" and cb["value"] > 0 and cb["cores"] >= 1 and cb["sample"]
+
+
+def test_committed_traffic_figures_are_present_and_plausible():
+    """bench.py reports `roofline.traffic` from the counter summaries under profiles/ (counters cannot be read inside
+    the timed run): the three default workloads' summaries must carry the figure, and it must lie between the
+    algorithmic bytes per launch and the share of re-reads the design document accounts for."""
+    import importlib.util
+
+    spec = importlib.util.spec_from_file_location("bench_module", BENCH)
+    bench = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(bench)
+    greedy = bench.read_traffic("greedy_rpl_kernel_laplace_10M_x_128_hbm_traffic.txt")
+    assert greedy is not None and 1.0 <= greedy / (10_000_000 * 580) < 1.01       # every row read once, codes written once
+    kmeans = bench.read_traffic("kmeans16_rpl_kernel_mixture_2M_x_64_kmeans16_hbm_traffic.txt")
+    assert kmeans is not None and 1.0 <= kmeans / (2_000_000 * 320) < 1.01
+    lookup = bench.read_traffic("sls_fused_w8_kernel_lookup_10M_x_128_sls_hbm_traffic.txt")
+    algorithmic = 34_093_552 * 76 + (1 << 20) * 520
+    assert lookup is not None and 2.0 < lookup / algorithmic < 3.0                 # 128-byte line fills on 68-byte records

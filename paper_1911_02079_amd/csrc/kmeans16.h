@@ -459,17 +459,22 @@ __global__ void __launch_bounds__(64 * WAVES) kmeans16_rpl_tail_kernel(KMeansArg
     kmeans16_rpl_body<D, Tin, true, WAVES>(a, d, scratch[WAVES == 1 ? 0 : threadIdx.x >> 6]);
 }
 
-// Waves per workgroup for a table of `rows` rows (see kmeans16_rpl_body).
-inline int kmeans16_waves_per_block(const KMeansArgs& a)
+// Waves per workgroup for a table of `rows` rows of (rounded-up) dimension D (see kmeans16_rpl_body): four while the
+// launch has at most one wave per SIMD less than the registers let a SIMD hold (three waves up to D = 88, two
+// beyond).  Measured, one-wave -> four-wave workgroups: D = 128, 65 536 rows 373 -> 276 us, 131 072 rows 402 -> 421 us;
+// D = 32, 131 072 rows 174 -> 141 us, 200 000 rows 239 -> 239 us.
+inline int kmeans16_waves_per_block(const KMeansArgs& a, int D)
 {
-    return a.waves == 1 || a.waves == 4 ? (int)a.waves : (a.rows <= (int64_t)2 * 1024 * 64 ? 4 : 1);
+    if (a.waves == 1 || a.waves == 4) return (int)a.waves;
+    const int64_t resident = D <= 88 ? 3 : 2;
+    return a.rows <= (resident - 1) * (int64_t)1024 * 64 ? 4 : 1;
 }
 
 // Launches the register-resident kernel for `dim` if there is one; returns false otherwise.
 template <typename Tin>
 inline bool launch_kmeans16_rpl(const KMeansArgs& a, int32_t dim, hipStream_t stream)
 {
-    const int waves = kmeans16_waves_per_block(a);
+    const int waves = kmeans16_waves_per_block(a, dim);
     const dim3 grid((unsigned)((a.rows + 64 * waves - 1) / (64 * waves))), block(64 * waves);
     switch (dim) {
 #define E4Q_CASE(D) \
@@ -490,7 +495,7 @@ template <typename Tin>
 inline bool launch_kmeans16_rpl_tail(const KMeansArgs& a, int32_t dim, hipStream_t stream)
 {
     if (dim <= kK || dim >= 128 || dim % 8 == 0) return false;
-    const int waves = kmeans16_waves_per_block(a);
+    const int waves = kmeans16_waves_per_block(a, (dim + 7) / 8 * 8);
     const dim3 grid((unsigned)((a.rows + 64 * waves - 1) / (64 * waves))), block(64 * waves);
     switch ((dim + 7) / 8 * 8) {
 #define E4Q_CASE(D) \

@@ -96,3 +96,47 @@ def test_capture_into_a_graph_and_replay(e4q, oracle_lib, rows, dim):
             assert torch.equal(got.view(torch.uint8), want.view(torch.uint8)), f"replay {k}"
     o = oracle_lib.quantize_rowwise_greedy(table[:2000].cpu().numpy(), 200, 0.16)
     assert np.array_equal(out[0][:2000].cpu().numpy(), o[0])
+
+
+def test_capture_a_batch_into_a_graph_and_replay(e4q, oracle_lib):
+    """The batch entry point under capture: 70 tables of dimension 64 go out as grouped launches whose table list is a
+    kernel argument of several kilobytes (it is copied at capture time: the replays must not depend on the descriptors
+    the call was given), three of dimension 100 as launches of their own."""
+    from paper_1911_02079_amd import synth
+
+    rng = np.random.default_rng(3)
+    tables = [synth.gaussian_table(int(rng.integers(1, 900)), 64, 0.1, seed=40 + k, device="cuda") for k in range(70)]
+    tables += [synth.gaussian_table(300 + k, 100, 0.1, seed=140 + k, device="cuda") for k in range(3)]
+    outs = [e4q.alloc_outputs(t.shape[0], t.shape[1], "cuda") for t in tables]
+
+    def path():
+        e4q.quantize_rowwise_greedy_batch(tables, 50, 0.16, out=outs)
+
+    path()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    say("capture a batch of 73 tables")
+    with torch.cuda.graph(graph, stream=side):
+        path()
+    torch.cuda.synchronize()
+    for k in range(3):
+        for j, t in enumerate(tables):
+            t.copy_(synth.gaussian_table(t.shape[0], t.shape[1], 0.1, seed=1000 * (k + 1) + j, device="cuda"))
+        path()
+        torch.cuda.synchronize()
+        eager = [tuple(x.clone() for x in o) for o in outs]
+        for o in outs:
+            for x in o:
+                x.zero_()
+        torch.cuda.synchronize()
+        say(f"replay {k}")
+        graph.replay()
+        torch.cuda.synchronize()
+        for j, (o, want) in enumerate(zip(outs, eager)):
+            for got, w in zip(o, want):
+                assert torch.equal(got.view(torch.uint8), w.view(torch.uint8)), f"replay {k}, table {j}"
+    for j in (0, 33, 69, 72):
+        o = oracle_lib.quantize_rowwise_greedy(tables[j].cpu().numpy(), 50, 0.16)
+        assert np.array_equal(outs[j][0].cpu().numpy(), o[0]) and np.array_equal(f16_bits(outs[j][1]), o[1])
